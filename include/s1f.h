@@ -1,0 +1,118 @@
+/* s1f — segment-wise causal attention for sequence-level 1F1B pipeline stages, MI355X (gfx950).
+ *
+ * C ABI of the library.  Plain pointers and sizes only; no framework types.
+ *
+ * The operations follow "Seq1F1B: Efficient Sequence-Level Pipeline Parallelism for Large Language
+ * Model Training" (arXiv 2406.03488):
+ *   - Section 3.1, Eq. 3: causal softmax attention; a token attends to itself and all earlier tokens,
+ *     scores scaled by 1/sqrt(head_dim).
+ *   - Section 3.1 (last paragraph) and Section 3.2: a sequence is cut into segments; the forward of a
+ *     segment needs the keys/values of all preceding tokens (the "prefix"); backward passes run in
+ *     reverse segment order and their gradients are accumulated so that the result equals that of the
+ *     unsplit sequence.
+ *   - Section 3.4, Eq. 7-8: segment lengths are chosen so that every segment costs the same FLOPs.
+ *
+ * Conventions common to all device entry points
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library allocates nothing,
+ *     keeps no pointer after return, and has no global state (re-entrant).
+ *   - Layout is [batch, head, sequence, head_dim] with head_dim contiguous; the other three strides
+ *     are passed in ELEMENTS through s1f_desc.  q, out, dout, dq share the q_* strides; k, v share the
+ *     kv_* strides; dk_prefix_acc, dv_prefix_acc share the kv_* strides too (in fp32 elements).
+ *     lse is a dense fp32 array [batch, n_q_heads, seg_len].
+ *   - Query head h reads key/value head h / (n_q_heads / n_kv_heads) (contiguous groups).
+ *   - Kernels are enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default stream) and
+ *     the call returns without synchronising.  Arguments are validated before anything is enqueued; on
+ *     an error status nothing has been launched and no output was touched.
+ *   - Every entry point returns an s1f_status; nothing throws or aborts across this boundary.
+ */
+#ifndef S1F_H
+#define S1F_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  S1F_OK = 0,
+  S1F_EINVAL = 1,       /* null pointer, non-positive size, inconsistent descriptor */
+  S1F_EUNSUPPORTED = 2, /* dtype / head_dim combination without a kernel */
+  S1F_ERANGE = 3,       /* segment does not fit: seg_off < 0, seg_len < 1, seg_off + seg_len > kv_capacity */
+  S1F_EDEVICE = 4       /* the HIP runtime reported an error at launch */
+} s1f_status;
+
+typedef enum {
+  S1F_F32 = 0, /* q, k, v, out, dout, dq are fp32; fp32 matrix arithmetic */
+  S1F_BF16 = 1 /* q, k, v, out, dout, dq are bf16; bf16 MFMA with fp32 accumulation; probabilities and
+                  score gradients are rounded to bf16 before their second product */
+} s1f_dtype;
+
+typedef struct {
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads; /* must divide n_q_heads */
+  int32_t head_dim;   /* 64, 80 or 128 */
+  int32_t dtype;      /* s1f_dtype; lse and the dK/dV accumulators are always fp32 */
+  int32_t reserved;   /* must be 0 */
+  int64_t q_stride_b, q_stride_h, q_stride_s;    /* elements; q_stride_s >= head_dim */
+  int64_t kv_stride_b, kv_stride_h, kv_stride_s; /* elements; kv_stride_s >= head_dim */
+  int64_t kv_capacity; /* rows allocated per head in k, v, dk_prefix_acc, dv_prefix_acc */
+} s1f_desc;
+
+/* Computation-wise partition (Section 3.4, Eq. 7-8).  HOST function, no device work.
+ *
+ * Writes n_seg + 1 boundaries 0 = b[0] < b[1] < ... < b[n_seg] = seq_len into the caller-owned HOST
+ * array `boundaries`; segment i (1-based) holds tokens b[i-1] .. b[i]-1.
+ * Cost model: Eq. 8 with P/L = 12 hidden^2, made additive over tokens so that the k costs of Eq. 7 can
+ * be equal: token t (1-based) costs w(t) = 6*hidden + t (units of 4*L*hidden FLOPs; the t is its
+ * causal attention over t keys), the first x tokens cost W(x) = 6*hidden*x + x(x+1)/2.  b[i] is the
+ * integer x minimising |n_seg*W(x) - i*W(seq_len)| (smaller x on a tie), then clamped so that every
+ * segment keeps at least one token.  `heads` is validated (must divide hidden) and otherwise unused.
+ * Errors: S1F_EINVAL for n_seg < 1, seq_len < n_seg, hidden < 1, heads < 1, hidden % heads != 0,
+ * boundaries == NULL, or sizes whose cost would overflow 2^62. */
+int s1f_partition(int64_t seq_len, int32_t n_seg, int32_t hidden, int32_t heads, int64_t *boundaries);
+
+/* Forward of one segment (Section 3.1 Eq. 3 restricted to the segment's rows; Section 3.2).
+ *
+ *   q_seg     [batch, n_q_heads, seg_len, head_dim]  queries of absolute rows seg_off .. seg_off+seg_len-1
+ *   k_prefix, v_prefix  point at row 0 of the caller's K/V cache; rows [0, seg_off+seg_len) must be
+ *             valid and already include the segment's own keys/values
+ *   out       [batch, n_q_heads, seg_len, head_dim]  overwritten (dtype of the descriptor)
+ *   lse       [batch, n_q_heads, seg_len] fp32, overwritten: natural-log sum-exp of the scaled scores
+ * Row r of the segment attends to keys j <= seg_off + r. */
+int s1f_seg_attn_fwd(const s1f_desc *desc, const void *q_seg, const void *k_prefix, const void *v_prefix,
+                     int64_t seg_off, int64_t seg_len, void *out, float *lse, void *hip_stream);
+
+/* Backward of one segment (derivative of Eq. 3; order and accumulation per Sections 3.1-3.2).
+ *
+ *   dout, q_seg, out, lse : the segment's upstream gradient and the tensors saved by the forward
+ *   dq        [batch, n_q_heads, seg_len, head_dim]  overwritten; complete after this call, since all
+ *             keys a row of the segment can see are in the prefix
+ *   dk_prefix_acc, dv_prefix_acc  fp32 [batch, n_kv_heads, kv_capacity, head_dim] (kv_* strides):
+ *             rows [0, seg_off+seg_len) are updated with += (each element by exactly one workgroup, no
+ *             atomics); rows beyond are not touched.  The caller zeroes them before the backward of the
+ *             LAST segment and calls segments in reverse order; after the call for segment i, rows
+ *             [seg_off, seg_off+seg_len) hold final gradients.
+ *   workspace device scratch of at least s1f_bwd_workspace_bytes(desc, seg_off, seg_len) bytes
+ *             (holds delta = rowsum(dout * out) in fp32); contents are undefined afterwards.
+ * Errors as above, plus S1F_EINVAL if workspace is NULL or workspace_bytes is too small. */
+int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
+                     const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
+                     int64_t seg_len, void *dq, float *dk_prefix_acc, float *dv_prefix_acc,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of device scratch s1f_seg_attn_bwd needs for this call shape (0 on invalid arguments). */
+size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len);
+
+/* Static, NUL-terminated description of a status code. */
+const char *s1f_strerror(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int s1f_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S1F_H */

@@ -1,0 +1,12 @@
+"""Python binding of libs1f.so: segment-wise causal attention for sequence-level 1F1B (Seq1F1B,
+arXiv 2406.03488) on MI355X.
+
+Argument marshalling only: every step runs in the library's HIP kernels.  PyTorch supplies device
+memory and the current stream.  There is no fallback: if the shared library is missing, importing the
+compute entry points raises.
+"""
+from .binding import (Desc, S1FError, bwd_workspace_bytes, library_path, load_library, partition,
+                      seg_attn_bwd, seg_attn_fwd, strerror, version)
+
+__all__ = ["Desc", "S1FError", "bwd_workspace_bytes", "library_path", "load_library", "partition",
+           "seg_attn_bwd", "seg_attn_fwd", "strerror", "version"]

@@ -1,0 +1,155 @@
+"""ctypes binding of the C ABI declared in include/s1f.h (same names, same argument order)."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libs1f.so")
+_lib = None
+
+S1F_F32, S1F_BF16 = 0, 1
+
+
+class S1FError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({strerror(status)})")
+
+
+class Desc(ctypes.Structure):
+    """Mirror of s1f_desc."""
+    _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64), ("q_stride_s", ctypes.c_int64),
+                ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_s", ctypes.c_int64),
+                ("kv_capacity", ctypes.c_int64)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libs1f.so (built in-tree by paper_2406_03488_amd.build).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} not found: build it with `python -m paper_2406_03488_amd.build` "
+                          "(there is no fallback implementation)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+    dp = ctypes.POINTER(Desc)
+    lib.s1f_partition.argtypes = [i64, i32, i32, i32, ctypes.POINTER(i64)]
+    lib.s1f_partition.restype = ctypes.c_int
+    lib.s1f_seg_attn_fwd.argtypes = [dp, vp, vp, vp, i64, i64, vp, vp, vp]
+    lib.s1f_seg_attn_fwd.restype = ctypes.c_int
+    lib.s1f_seg_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
+    lib.s1f_seg_attn_bwd.restype = ctypes.c_int
+    lib.s1f_bwd_workspace_bytes.argtypes = [dp, i64, i64]
+    lib.s1f_bwd_workspace_bytes.restype = sz
+    lib.s1f_strerror.argtypes = [ctypes.c_int]
+    lib.s1f_strerror.restype = ctypes.c_char_p
+    lib.s1f_version.argtypes = []
+    lib.s1f_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def strerror(status: int) -> str:
+    return load_library().s1f_strerror(int(status)).decode()
+
+
+def version() -> int:
+    return int(load_library().s1f_version())
+
+
+def partition(seq_len: int, n_seg: int, hidden: int, heads: int):
+    """s1f_partition: list of n_seg + 1 boundaries."""
+    lib = load_library()
+    out = (ctypes.c_int64 * (max(int(n_seg), 0) + 1))()
+    rc = lib.s1f_partition(int(seq_len), int(n_seg), int(hidden), int(heads), out)
+    if rc != 0:
+        raise S1FError(rc, "s1f_partition")
+    return list(out)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return S1F_F32
+    if t.dtype == torch.bfloat16:
+        return S1F_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def make_desc(q_like, kv_like) -> Desc:
+    """Descriptor from a [B, Hq, S, D] query-shaped tensor and a [B, Hkv, C, D] prefix-shaped tensor."""
+    if q_like.dim() != 4 or kv_like.dim() != 4 or q_like.stride(3) != 1 or kv_like.stride(3) != 1:
+        raise ValueError("expected [batch, heads, seq, head_dim] tensors with contiguous head_dim")
+    b, hq, _, d = q_like.shape
+    return Desc(batch=b, n_q_heads=hq, n_kv_heads=kv_like.shape[1], head_dim=d, dtype=_dtype_code(q_like), reserved=0,
+                q_stride_b=q_like.stride(0), q_stride_h=q_like.stride(1), q_stride_s=q_like.stride(2),
+                kv_stride_b=kv_like.stride(0), kv_stride_h=kv_like.stride(1), kv_stride_s=kv_like.stride(2),
+                kv_capacity=kv_like.shape[2])
+
+
+def _stream_ptr():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _same_layout(ref, *others):
+    for t in others:
+        if t.shape != ref.shape or t.stride() != ref.stride() or t.dtype != ref.dtype:
+            raise ValueError("tensors sharing a stride set must have identical shape, strides and dtype")
+
+
+def seg_attn_fwd(q_seg, k_prefix, v_prefix, seg_off: int, out, lse):
+    """s1f_seg_attn_fwd on torch device tensors.
+
+    q_seg/out [B, Hq, seg_len, D]; k_prefix/v_prefix [B, Hkv, capacity, D] (row 0 of the cache);
+    lse [B, Hq, seg_len] fp32 contiguous.  Enqueued on torch's current stream.
+    """
+    lib = load_library()
+    _same_layout(q_seg, out)
+    _same_layout(k_prefix, v_prefix)
+    if not lse.is_contiguous() or lse.shape != q_seg.shape[:3]:
+        raise ValueError("lse must be a contiguous [B, Hq, seg_len] fp32 tensor")
+    desc = make_desc(q_seg, k_prefix)
+    rc = lib.s1f_seg_attn_fwd(ctypes.byref(desc), q_seg.data_ptr(), k_prefix.data_ptr(), v_prefix.data_ptr(),
+                              int(seg_off), int(q_seg.shape[2]), out.data_ptr(), lse.data_ptr(), _stream_ptr())
+    if rc != 0:
+        raise S1FError(rc, "s1f_seg_attn_fwd")
+
+
+def bwd_workspace_bytes(q_seg, k_prefix, seg_off: int) -> int:
+    desc = make_desc(q_seg, k_prefix)
+    return int(load_library().s1f_bwd_workspace_bytes(ctypes.byref(desc), int(seg_off), int(q_seg.shape[2])))
+
+
+def seg_attn_bwd(dout, q_seg, k_prefix, v_prefix, out, lse, seg_off: int, dq, dk_prefix_acc, dv_prefix_acc, workspace):
+    """s1f_seg_attn_bwd on torch device tensors.
+
+    dk_prefix_acc/dv_prefix_acc are fp32 tensors with the shape and strides of k_prefix; workspace is any
+    device tensor of at least bwd_workspace_bytes(...) bytes.
+    """
+    lib = load_library()
+    _same_layout(q_seg, dout, out, dq)
+    _same_layout(k_prefix, v_prefix)
+    _same_layout(dk_prefix_acc, dv_prefix_acc)
+    if dk_prefix_acc.shape != k_prefix.shape or dk_prefix_acc.stride() != k_prefix.stride():
+        raise ValueError("gradient accumulators must have the shape and strides of k_prefix")
+    import torch
+    if dk_prefix_acc.dtype != torch.float32 or lse.dtype != torch.float32:
+        raise TypeError("accumulators and lse are fp32")
+    if not lse.is_contiguous() or lse.shape != q_seg.shape[:3]:
+        raise ValueError("lse must be a contiguous [B, Hq, seg_len] fp32 tensor")
+    desc = make_desc(q_seg, k_prefix)
+    rc = lib.s1f_seg_attn_bwd(ctypes.byref(desc), dout.data_ptr(), q_seg.data_ptr(), k_prefix.data_ptr(),
+                              v_prefix.data_ptr(), out.data_ptr(), lse.data_ptr(), int(seg_off), int(q_seg.shape[2]),
+                              dq.data_ptr(), dk_prefix_acc.data_ptr(), dv_prefix_acc.data_ptr(),
+                              workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr())
+    if rc != 0:
+        raise S1FError(rc, "s1f_seg_attn_bwd")

@@ -1,0 +1,207 @@
+// Device-side building blocks shared by the three attention kernels (gfx950 / CDNA4 only).
+//
+// Vocabulary used throughout:
+//   wave      64 lanes; lane = 32*g + ln with g in {0,1}, ln in 0..31
+//   block     a 32x32 fp32 MFMA result held as 16 registers per lane: register v of lane (g, ln) is
+//             element (row 8*(v/4) + 4*g + v%4, column ln)
+//   fragment  what one lane feeds to one MFMA as A (row ln) or B (column ln) operand: EPL consecutive
+//             elements of the contraction index starting at EPL*g; one MFMA contracts KSTEP = 2*EPL
+//   slab      KSTEP consecutive MFMA contraction slots taken from a block's ROW index, so that a block
+//             can be fed back as an operand without any cross-lane movement: slot (g, e) of slab t is
+//             block row r(t, g, e) = 8*((EPL*t+e)/4) + 4*g + (EPL*t+e)%4, i.e. register EPL*t + e.
+//             The other operand is read from LDS in the same row order.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace s1f {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define S1F_DEV __device__ __forceinline__
+#define S1F_LDS(ptr_type, p) ((__attribute__((address_space(3))) ptr_type *)(p))
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int EPL = 1;    // elements per lane per MFMA operand
+  static constexpr int CE = 4;     // elements per 16-byte chunk
+  typedef float Frag;
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int EPL = 8;
+  static constexpr int CE = 8;
+  typedef bf16x8 Frag;
+};
+
+// D(32x32) += A(32xKSTEP) * B(KSTEPx32)
+S1F_DEV f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+S1F_DEV f32x16 mma(float a, float b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+
+S1F_DEV float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
+S1F_DEV float xor32(float x) { return __shfl_xor(x, 32, 64); }            // partner lane of the other half-wave
+
+template <typename T> S1F_DEV typename Elem<T>::Frag load_frag_global(const T *p);
+template <> S1F_DEV float load_frag_global<float>(const float *p) { return *p; }
+template <> S1F_DEV bf16x8 load_frag_global<bf16_t>(const bf16_t *p) { return *reinterpret_cast<const bf16x8 *>(p); }
+
+template <typename T> S1F_DEV float frag_dot(typename Elem<T>::Frag a, typename Elem<T>::Frag b);
+template <> S1F_DEV float frag_dot<float>(float a, float b) { return a * b; }
+template <> S1F_DEV float frag_dot<bf16_t>(bf16x8 a, bf16x8 b) {
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s += (float)a[e] * (float)b[e];
+  return s;
+}
+
+// Slab t of a block as an MFMA operand (rounds to bf16 in bf16 mode).
+template <typename T> S1F_DEV typename Elem<T>::Frag block_slab(const f32x16 &c, int t);
+template <> S1F_DEV float block_slab<float>(const f32x16 &c, int t) { return c[t]; }
+template <> S1F_DEV bf16x8 block_slab<bf16_t>(const f32x16 &c, int t) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (bf16_t)c[8 * t + e];
+  return r;
+}
+
+constexpr int pow2_at_least(int x) { int p = 1; while (p < x) p *= 2; return p; }
+
+// A [ROWS x D] tile of T in LDS, rows of RS 16-byte chunks, chunk c of row r stored at position
+// c ^ swz(r).  The swizzle makes both access patterns below bank-conflict free without padding:
+// 16 lanes reading the same chunk of 16 consecutive rows, and 32 lanes reading 4 consecutive rows x 4
+// consecutive chunks (the transposing read).
+template <typename T, int ROWS_, int D_> struct LdsTile {
+  static constexpr int ROWS = ROWS_;
+  static constexpr int D = D_;
+  static constexpr int CE = Elem<T>::CE;
+  static constexpr int DPAD = (D + 31) / 32 * 32;
+  static constexpr int CPR = D / CE;                       // chunks per row holding data
+  static constexpr int RS = pow2_at_least(DPAD / CE);      // row stride in chunks
+  static constexpr int BYTES = ROWS * RS * 16;
+  static_assert(D % CE == 0, "head_dim must be a whole number of 16-byte chunks");
+  static_assert(RS >= 8, "row too short for the swizzle");
+
+  S1F_DEV static int swz(int r) {
+    if (RS >= 16) return ((r & 3) << 2) | ((r >> 2) & 3);
+    return (((r >> 1) & 1) << 2) | ((r >> 2) & 3);
+  }
+  S1F_DEV static int chunk_off(int r, int c) { return (r * RS + (c ^ swz(r))) * 16; }   // bytes
+
+  // Operand fragment with the contraction running along D: lane reads row `row`, elements
+  // [KSTEP*ks + EPL*g, +EPL).
+  S1F_DEV static typename Elem<T>::Frag nat_frag(const char *tile, int row, int ks, int g);
+  // Operand fragment with the contraction running along the tile's rows (slab t of the 32-row block
+  // starting at row32), for operand index (row for A, column for B) d = 32*db + ln.
+  S1F_DEV static typename Elem<T>::Frag tr_frag(const char *tile, int row32, int t, int db, int lane);
+};
+
+template <typename Tile> struct TileOps;
+
+template <int ROWS, int D> struct TileOps<LdsTile<float, ROWS, D>> {
+  typedef LdsTile<float, ROWS, D> TL;
+  S1F_DEV static float nat(const char *tile, int row, int ks, int g) {
+    const int d = 2 * ks + g;
+    return *reinterpret_cast<const float *>(tile + TL::chunk_off(row, d >> 2) + 4 * (d & 3));
+  }
+  S1F_DEV static float tr(const char *tile, int row32, int t, int db, int lane) {
+    const int g = lane >> 5, ln = lane & 31;
+    const int row = row32 + 8 * (t >> 2) + 4 * g + (t & 3);
+    const int d = 32 * db + ln;
+    return *reinterpret_cast<const float *>(tile + TL::chunk_off(row, d >> 2) + 4 * (d & 3));
+  }
+};
+
+template <int ROWS, int D> struct TileOps<LdsTile<bf16_t, ROWS, D>> {
+  typedef LdsTile<bf16_t, ROWS, D> TL;
+  S1F_DEV static bf16x8 nat(const char *tile, int row, int ks, int g) {
+    return *reinterpret_cast<const bf16x8 *>(tile + TL::chunk_off(row, 2 * ks + g));
+  }
+  // ds_read_b64_tr_b16: within each group of 16 lanes, lane i supplies the address of 4 consecutive
+  // 16-bit elements (row i/4 of a 4x16 matrix, columns 4*(i%4)..+3) and lane n receives column n of
+  // that matrix (4 rows).  Two reads give the 8 contraction slots of a slab: rows 16t+4g+{0..3} and
+  // 16t+8+4g+{0..3} of the 32-row block, for column d = 32*db + 16*(b&1) + n, b = lane/16.
+  S1F_DEV static bf16x8 tr(const char *tile, int row32, int t, int db, int lane) {
+    const int i = lane & 15, b = lane >> 4, g = lane >> 5;
+    const int c = 4 * db + 2 * (b & 1) + ((i & 3) >> 1);
+    const int sub = (i & 1) * 8;
+    const int r0 = row32 + 16 * t + 4 * g + (i >> 2);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(S1F_LDS(s16x4, tile + TL::chunk_off(r0, c) + sub));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(S1F_LDS(s16x4, tile + TL::chunk_off(r0 + 8, c) + sub));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+  }
+};
+
+template <typename T, int ROWS, int D>
+S1F_DEV typename Elem<T>::Frag LdsTile<T, ROWS, D>::nat_frag(const char *tile, int row, int ks, int g) {
+  return TileOps<LdsTile<T, ROWS, D>>::nat(tile, row, ks, g);
+}
+template <typename T, int ROWS, int D>
+S1F_DEV typename Elem<T>::Frag LdsTile<T, ROWS, D>::tr_frag(const char *tile, int row32, int t, int db, int lane) {
+  return TileOps<LdsTile<T, ROWS, D>>::tr(tile, row32, t, db, lane);
+}
+
+// Register-staged copy of a [ROWS x D] tile from global memory (row stride in elements) into an
+// LdsTile, by NT threads, 16 bytes per access.  Rows >= rows_valid are filled with zeros.
+template <typename T, int ROWS, int D, int NT> struct TileCopy {
+  typedef LdsTile<T, ROWS, D> TL;
+  static constexpr int TOTAL = ROWS * TL::CPR;
+  static constexpr int PER = (TOTAL + NT - 1) / NT;
+  u32x4 regs[PER];
+
+  S1F_DEV void load(const T *base, int64_t row_stride, int rows_valid, int tid) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int id = tid + i * NT;
+      const int r = id / TL::CPR, c = id % TL::CPR;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if ((TOTAL % NT == 0 || id < TOTAL) && r < rows_valid)
+        v = *reinterpret_cast<const u32x4 *>(base + (int64_t)r * row_stride + c * TL::CE);
+      regs[i] = v;
+    }
+  }
+  S1F_DEV void store(char *tile, int tid) const {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int id = tid + i * NT;
+      const int r = id / TL::CPR, c = id % TL::CPR;
+      if (TOTAL % NT == 0 || id < TOTAL) *reinterpret_cast<u32x4 *>(tile + TL::chunk_off(r, c)) = regs[i];
+    }
+  }
+};
+
+// Store 4 consecutive head_dim elements of one row.
+template <typename T> S1F_DEV void store4(T *p, float a, float b, float c, float d);
+template <> S1F_DEV void store4<float>(float *p, float a, float b, float c, float d) {
+  *reinterpret_cast<f32x4 *>(p) = f32x4{a, b, c, d};
+}
+template <> S1F_DEV void store4<bf16_t>(bf16_t *p, float a, float b, float c, float d) {
+  bf16x4 r = {(bf16_t)a, (bf16_t)b, (bf16_t)c, (bf16_t)d};
+  *reinterpret_cast<bf16x4 *>(p) = r;
+}
+
+// Arguments common to the three kernels (all strides in elements of the tensor they index).
+struct AttnArgs {
+  const void *q, *k, *v, *out, *dout;   // out: written by fwd, read by bwd
+  void *out_w, *dq;
+  float *lse;                            // [batch, Hq, seg_len]
+  float *delta;                          // [batch, Hq, seg_len] workspace (bwd)
+  float *dk_acc, *dv_acc;
+  int64_t q_sb, q_sh, q_ss;
+  int64_t kv_sb, kv_sh, kv_ss;
+  int32_t seg_off, seg_len;
+  int32_t n_q_heads, group;              // group = Hq / Hkv
+  float scale;                           // 1/sqrt(head_dim)
+};
+
+}  // namespace s1f

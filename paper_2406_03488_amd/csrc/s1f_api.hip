@@ -1,0 +1,158 @@
+// C ABI of the library: argument validation and kernel dispatch.  See include/s1f.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "attn_bwd.hpp"
+#include "attn_fwd.hpp"
+#include "s1f.h"
+
+namespace {
+using namespace s1f;
+
+// Tile shapes per element type: query blocks per wave (NQ), key blocks per wave (NK), keys per staged
+// K/V tile (BN), rows per staged Q/dO tile (BQ).
+template <typename T> struct Shape;
+template <> struct Shape<bf16_t> { static constexpr int NQ = 2, BN = 64, NK = 1, BQ = 64; };
+template <> struct Shape<float>  { static constexpr int NQ = 1, BN = 32, NK = 1, BQ = 32; };
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_desc(const s1f_desc *d) {
+  if (d == nullptr) return S1F_EINVAL;
+  if (d->batch < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_q_heads % d->n_kv_heads != 0) return S1F_EINVAL;
+  if (d->reserved != 0 || d->kv_capacity < 1) return S1F_EINVAL;
+  if (d->dtype != S1F_F32 && d->dtype != S1F_BF16) return S1F_EUNSUPPORTED;
+  if (d->head_dim != 64 && d->head_dim != 80 && d->head_dim != 128) return S1F_EUNSUPPORTED;
+  if (d->batch > 65535 || d->n_q_heads > 65535) return S1F_EUNSUPPORTED;
+  // 16-byte vector accesses: every row must start on a 16-byte boundary
+  const int64_t ce = d->dtype == S1F_BF16 ? 8 : 4;
+  const int64_t s[6] = {d->q_stride_b, d->q_stride_h, d->q_stride_s, d->kv_stride_b, d->kv_stride_h, d->kv_stride_s};
+  for (int i = 0; i < 6; ++i)
+    if (s[i] < 0 || s[i] % ce != 0) return S1F_EINVAL;
+  if (d->q_stride_s < d->head_dim || d->kv_stride_s < d->head_dim) return S1F_EINVAL;
+  return S1F_OK;
+}
+
+int check_seg(const s1f_desc *d, int64_t seg_off, int64_t seg_len) {
+  if (seg_off < 0 || seg_len < 1 || seg_off + seg_len > d->kv_capacity) return S1F_ERANGE;
+  if (seg_off + seg_len > (int64_t(1) << 30)) return S1F_ERANGE;   // kernels index rows with 32-bit integers
+  return S1F_OK;
+}
+
+AttnArgs make_args(const s1f_desc *d, int64_t seg_off, int64_t seg_len) {
+  AttnArgs a = {};
+  a.q_sb = d->q_stride_b; a.q_sh = d->q_stride_h; a.q_ss = d->q_stride_s;
+  a.kv_sb = d->kv_stride_b; a.kv_sh = d->kv_stride_h; a.kv_ss = d->kv_stride_s;
+  a.seg_off = (int32_t)seg_off; a.seg_len = (int32_t)seg_len;
+  a.n_q_heads = d->n_q_heads; a.group = d->n_q_heads / d->n_kv_heads;
+  a.scale = (float)(1.0 / std::sqrt((double)d->head_dim));
+  return a;
+}
+
+template <typename K> int launch(K kernel, dim3 grid, int lds_bytes, const AttnArgs &a, hipStream_t st) {
+  if (lds_bytes > 64 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            lds_bytes) != hipSuccess)
+      return S1F_EDEVICE;
+  }
+  hipLaunchKernelGGL(kernel, grid, dim3(256), lds_bytes, st, a);
+  return hipGetLastError() == hipSuccess ? S1F_OK : S1F_EDEVICE;
+}
+
+template <typename T, int D> int fwd_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
+  typedef Shape<T> S;
+  typedef FwdCfg<T, D, S::NQ, S::BN> Cfg;
+  const dim3 grid((a.seg_len + Cfg::BM - 1) / Cfg::BM, d->n_q_heads, d->batch);
+  return launch(seg_attn_fwd_kernel<T, D, S::NQ, S::BN>, grid, Cfg::LDS_BYTES, a, st);
+}
+
+template <typename T, int D> int bwd_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
+  typedef Shape<T> S;
+  typedef BwdDqCfg<T, D, S::NQ, S::BN> QC;
+  typedef BwdDkdvCfg<T, D, S::NK, S::BQ> KC;
+  const dim3 gq((a.seg_len + QC::BM - 1) / QC::BM, d->n_q_heads, d->batch);
+  int rc = launch(seg_attn_bwd_dq_kernel<T, D, S::NQ, S::BN>, gq, QC::LDS_BYTES, a, st);
+  if (rc != S1F_OK) return rc;
+  const int kv_len = a.seg_off + a.seg_len;
+  const dim3 gk((kv_len + KC::BNW - 1) / KC::BNW, d->n_kv_heads, d->batch);
+  return launch(seg_attn_bwd_dkdv_kernel<T, D, S::NK, S::BQ>, gk, KC::LDS_BYTES, a, st);
+}
+
+template <template <typename, int> class F> struct Dispatch;
+
+#define S1F_DISPATCH(fn, d, ...)                                                        \
+  do {                                                                                  \
+    if ((d)->dtype == S1F_BF16) {                                                       \
+      switch ((d)->head_dim) {                                                          \
+        case 64: return fn<bf16_t, 64>(__VA_ARGS__);                                    \
+        case 80: return fn<bf16_t, 80>(__VA_ARGS__);                                    \
+        case 128: return fn<bf16_t, 128>(__VA_ARGS__);                                  \
+      }                                                                                 \
+    } else {                                                                            \
+      switch ((d)->head_dim) {                                                          \
+        case 64: return fn<float, 64>(__VA_ARGS__);                                     \
+        case 80: return fn<float, 80>(__VA_ARGS__);                                     \
+        case 128: return fn<float, 128>(__VA_ARGS__);                                   \
+      }                                                                                 \
+    }                                                                                   \
+    return S1F_EUNSUPPORTED;                                                            \
+  } while (0)
+
+}  // namespace
+
+extern "C" int s1f_seg_attn_fwd(const s1f_desc *desc, const void *q_seg, const void *k_prefix, const void *v_prefix,
+                                int64_t seg_off, int64_t seg_len, void *out, float *lse, void *hip_stream) {
+  int rc = check_desc(desc);
+  if (rc != S1F_OK) return rc;
+  if (!q_seg || !k_prefix || !v_prefix || !out || !lse) return S1F_EINVAL;
+  if (!aligned16(q_seg) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(out)) return S1F_EINVAL;
+  rc = check_seg(desc, seg_off, seg_len);
+  if (rc != S1F_OK) return rc;
+  AttnArgs a = make_args(desc, seg_off, seg_len);
+  a.q = q_seg; a.k = k_prefix; a.v = v_prefix; a.out_w = out; a.lse = lse;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  S1F_DISPATCH(fwd_impl, desc, desc, a, st);
+}
+
+extern "C" size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len) {
+  if (check_desc(desc) != S1F_OK || check_seg(desc, seg_off, seg_len) != S1F_OK) return 0;
+  return (size_t)desc->batch * (size_t)desc->n_q_heads * (size_t)seg_len * sizeof(float);
+}
+
+extern "C" int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
+                                const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
+                                int64_t seg_len, void *dq, float *dk_prefix_acc, float *dv_prefix_acc,
+                                void *workspace, size_t workspace_bytes, void *hip_stream) {
+  int rc = check_desc(desc);
+  if (rc != S1F_OK) return rc;
+  if (!dout || !q_seg || !k_prefix || !v_prefix || !out || !lse || !dq || !dk_prefix_acc || !dv_prefix_acc ||
+      !workspace)
+    return S1F_EINVAL;
+  if (!aligned16(dout) || !aligned16(q_seg) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(out) ||
+      !aligned16(dq) || !aligned16(dk_prefix_acc) || !aligned16(dv_prefix_acc) || !aligned16(workspace))
+    return S1F_EINVAL;
+  rc = check_seg(desc, seg_off, seg_len);
+  if (rc != S1F_OK) return rc;
+  if (workspace_bytes < s1f_bwd_workspace_bytes(desc, seg_off, seg_len)) return S1F_EINVAL;
+  AttnArgs a = make_args(desc, seg_off, seg_len);
+  a.q = q_seg; a.k = k_prefix; a.v = v_prefix; a.out = out; a.dout = dout; a.dq = dq;
+  a.lse = const_cast<float *>(lse); a.delta = reinterpret_cast<float *>(workspace);
+  a.dk_acc = dk_prefix_acc; a.dv_acc = dv_prefix_acc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  S1F_DISPATCH(bwd_impl, desc, desc, a, st);
+}
+
+extern "C" const char *s1f_strerror(int status) {
+  switch (status) {
+    case S1F_OK: return "ok";
+    case S1F_EINVAL: return "invalid argument (null or misaligned pointer, bad size or stride, workspace too small)";
+    case S1F_EUNSUPPORTED: return "unsupported dtype or head_dim (supported: f32/bf16 with head_dim 64, 80, 128)";
+    case S1F_ERANGE: return "segment out of range (seg_off < 0, seg_len < 1 or seg_off + seg_len > kv_capacity)";
+    case S1F_EDEVICE: return "HIP runtime error at kernel launch";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int s1f_version(void) { return 100; }
