@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the segmented causal attention hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic sequence: the host partitioner, the forward of
+every segment in order, the zero-fill of the fp32 dK/dV accumulators, and the backward of every segment
+in reverse order (Sections 3.1, 3.2 and 3.4 of the Seq1F1B paper).  Inputs are resident in HBM before
+the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b|2.7b|30b|30b-uniform|gqa|tiny]
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3     # MI355X fp32 matrix
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="7b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-unsegmented", action="store_true")
+    return ap.parse_args()
+
+
+def seg_pairs(bounds):
+    """Causal (query, key) pairs per head of each segment."""
+    return [(b - a) * a + (b - a) * (b - a + 1) // 2 for a, b in zip(bounds[:-1], bounds[1:])]
+
+
+class Stage:
+    """Device buffers of one pipeline stage's attention for one sequence, and the step that uses them."""
+
+    def __init__(self, w, torch, s1f):
+        self.w, self.torch, self.s1f = w, torch, s1f
+        dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(w.seed)
+        n, d = w.seq_len, w.head_dim
+
+        def rnd(h):
+            return torch.randn((1, h, n, d), generator=gen, device="cuda", dtype=torch.float32).to(dt)
+
+        self.q, self.dout = rnd(w.n_q_heads), rnd(w.n_q_heads)
+        self.k, self.v = rnd(w.n_kv_heads), rnd(w.n_kv_heads)
+        self.out = torch.empty_like(self.q)
+        self.dq = torch.empty_like(self.q)
+        self.dk = torch.empty((1, w.n_kv_heads, n, d), device="cuda", dtype=torch.float32)
+        self.dv = torch.empty_like(self.dk)
+        self.lse_flat = torch.empty(w.n_q_heads * n, device="cuda", dtype=torch.float32)
+        self.ws = torch.empty(w.n_q_heads * n, device="cuda", dtype=torch.float32)
+        self.events = []     # (kind, segment, start, end) recorded inside timed steps
+
+    def boundaries(self, n_seg=None, kind=None):
+        w = self.w
+        n_seg = w.n_seg if n_seg is None else n_seg
+        kind = w.partition if kind is None else kind
+        if kind == "cwp":
+            return self.s1f.partition(w.seq_len, n_seg, w.hidden, w.n_q_heads)
+        return [(i * w.seq_len) // n_seg for i in range(n_seg + 1)]
+
+    def step(self, n_seg=None, kind=None, record=False):
+        torch, s1f, w = self.torch, self.s1f, self.w
+        bounds = self.boundaries(n_seg, kind)
+        segs = []
+        off = 0
+        for a, b in zip(bounds[:-1], bounds[1:]):
+            lse = self.lse_flat[off:off + w.n_q_heads * (b - a)].view(1, w.n_q_heads, b - a)
+            off += w.n_q_heads * (b - a)
+            segs.append((a, b, lse))
+
+        def timed(kind_, i, fn):
+            if not record:
+                fn()
+                return
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record()
+            self.events.append((kind_, i, e0, e1))
+
+        for i, (a, b, lse) in enumerate(segs):
+            timed("fwd", i, lambda: s1f.seg_attn_fwd(self.q[:, :, a:b], self.k, self.v, a, self.out[:, :, a:b], lse))
+        self.dk.zero_(); self.dv.zero_()
+        for i in reversed(range(len(segs))):
+            a, b, lse = segs[i]
+            qs, dos = self.q[:, :, a:b], self.dout[:, :, a:b]
+            timed("bwd_dq", i, lambda: s1f.seg_attn_bwd_dq(dos, qs, self.k, self.v, self.out[:, :, a:b], lse, a,
+                                                            self.dq[:, :, a:b], self.ws))
+            timed("bwd_dkdv", i, lambda: s1f.seg_attn_bwd_dkdv(dos, qs, self.k, self.v, lse, a, self.dk, self.dv,
+                                                                self.ws))
+        return bounds
+
+    def run(self, steps, warmup, **kw):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step(**kw)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step(record=True, **kw)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def cpu_baseline(stage, torch):
+    """The row oracle, as it stands, timed on this machine's host cores on a bounded sample of the workload:
+    one head, the first `ns` tokens, full causal forward + backward."""
+    from oracle import rows
+    w = stage.w
+    ns = min(w.seq_len, 8192 if w.head_dim >= 128 else 8192)
+    g = 0
+    q = stage.q[0, 0:1, :ns].float().cpu().numpy()
+    do = stage.dout[0, 0:1, :ns].float().cpu().numpy()
+    k = stage.k[0, g:g + 1, :ns].float().cpu().numpy()
+    v = stage.v[0, g:g + 1, :ns].float().cpu().numpy()
+    rows.build()
+    t0 = time.perf_counter()
+    rows.forward_rows(q, k, v, 0, 0, ns)
+    rows.dq_rows(q, k, v, do, 0, 0, ns)
+    rows.dkdv_keys(q, k, v, do, 0, 0, ns)
+    dt = time.perf_counter() - t0
+    flops = 14.0 * w.head_dim * (ns * (ns + 1) // 2)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": rows.threads(), "kind": "oracle",
+            "sample": f"fp64 row oracle, one head, first {ns} tokens of the {w.name} workload, full causal "
+                      f"forward+backward ({dt:.1f} s)", "seconds": dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path has no collectives and this build runs on a single MI355X; "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import s1f_synth as S
+    import paper_2406_03488_amd as s1f
+    s1f.load_library()            # fails loudly if the HIP library is missing; there is no fallback
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    w = S.WORKLOADS[args.workload]
+    stage = Stage(w, torch, s1f)
+    ms = stage.run(args.steps, args.warmup)
+    bounds = stage.boundaries()
+    pairs = seg_pairs(bounds)
+    d, hq = w.head_dim, w.n_q_heads
+    tot_pairs = sum(pairs)
+    assert tot_pairs == w.seq_len * (w.seq_len + 1) // 2
+    flops = 14.0 * d * hq * tot_pairs
+    peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
+
+    # per-kernel durations from the events recorded inside the timed steps
+    per = {"fwd": [0.0, 0, 4.0], "bwd_dq": [0.0, 0, 2.0], "bwd_dkdv": [0.0, 0, 8.0]}   # ms, launches, flops/(pair*D)
+    seg_ms = {}
+    for kind, i, e0, e1 in stage.events:
+        t = e0.elapsed_time(e1)
+        per[kind][0] += t; per[kind][1] += 1
+        seg_ms.setdefault(kind, [0.0] * len(pairs))[i] += t / args.steps
+    kernels = {}
+    for kind, (t, cnt, fpp) in per.items():
+        alg = fpp * d * hq * tot_pairs * args.steps          # algorithmic flops over all timed launches
+        kernels[kind] = {"avg_launch_ms": t / cnt, "launches_per_step": cnt // args.steps,
+                         "alg_tflops": alg / (t * 1e-3) / 1e12, "ms_per_step": t / args.steps}
+    dom = max(kernels, key=lambda kk: kernels[kk]["ms_per_step"])
+    roofline = {"bound": "mfma", "kernel": {"fwd": "seg_attn_fwd_kernel", "bwd_dq": "seg_attn_bwd_dq_kernel",
+                                            "bwd_dkdv": "seg_attn_bwd_dkdv_kernel"}[dom],
+                "achieved": kernels[dom]["alg_tflops"], "peak": peak, "unit": "TFLOP/s",
+                "frac": kernels[dom]["alg_tflops"] / peak, "traffic": None,
+                "avg_launch_ms": kernels[dom]["avg_launch_ms"]}
+
+    result = {
+        "metric": "segmented causal attn fwd+bwd TFLOP/s on 1 GPU; % of bf16 MFMA peak",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "seq_len": w.seq_len, "n_seg": w.n_seg, "partition": w.partition,
+                   "n_q_heads": hq, "n_kv_heads": w.n_kv_heads, "head_dim": d, "boundaries": bounds},
+        "pct_of_peak": 100.0 * flops / (ms * 1e-3) / 1e12 / peak,
+        "fwd_tflops": 4.0 * d * hq * tot_pairs / (kernels["fwd"]["ms_per_step"] * 1e-3) / 1e12,
+        "bwd_tflops": 10.0 * d * hq * tot_pairs /
+                      ((kernels["bwd_dq"]["ms_per_step"] + kernels["bwd_dkdv"]["ms_per_step"]) * 1e-3) / 1e12,
+        "kernels": kernels, "segment_ms": seg_ms, "roofline": roofline,
+    }
+    if not args.no_unsegmented:
+        stage.events = []
+        ms1 = stage.run(max(2, args.steps // 3), 1, n_seg=1, kind="uniform")
+        result["unsegmented_ms"] = ms1
+        result["segmentation_overhead"] = ms / ms1 - 1.0
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(stage, torch)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

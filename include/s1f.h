@@ -103,6 +103,19 @@ int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const void *q_seg, 
                      int64_t seg_len, void *dq, float *dk_prefix_acc, float *dv_prefix_acc,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The two halves of s1f_seg_attn_bwd as separate calls (same arguments, same validation), for callers
+ * that schedule or time them separately; s1f_seg_attn_bwd is exactly _dq followed by _dkdv on one stream.
+ *   s1f_seg_attn_bwd_dq    overwrites dq and writes delta = rowsum(dout * out) into workspace
+ *   s1f_seg_attn_bwd_dkdv  reads lse and the delta left in workspace by _dq for the same segment, and
+ *                          updates dk_prefix_acc / dv_prefix_acc */
+int s1f_seg_attn_bwd_dq(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
+                        const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
+                        int64_t seg_len, void *dq, void *workspace, size_t workspace_bytes, void *hip_stream);
+int s1f_seg_attn_bwd_dkdv(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
+                          const void *v_prefix, const float *lse, int64_t seg_off, int64_t seg_len,
+                          float *dk_prefix_acc, float *dv_prefix_acc, const void *workspace,
+                          size_t workspace_bytes, void *hip_stream);
+
 /* Bytes of device scratch s1f_seg_attn_bwd needs for this call shape (0 on invalid arguments). */
 size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len);
 

@@ -47,6 +47,10 @@ def load_library():
     lib.s1f_seg_attn_fwd.restype = ctypes.c_int
     lib.s1f_seg_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
     lib.s1f_seg_attn_bwd.restype = ctypes.c_int
+    lib.s1f_seg_attn_bwd_dq.argtypes = [dp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
+    lib.s1f_seg_attn_bwd_dq.restype = ctypes.c_int
+    lib.s1f_seg_attn_bwd_dkdv.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, sz, vp]
+    lib.s1f_seg_attn_bwd_dkdv.restype = ctypes.c_int
     lib.s1f_bwd_workspace_bytes.argtypes = [dp, i64, i64]
     lib.s1f_bwd_workspace_bytes.restype = sz
     lib.s1f_strerror.argtypes = [ctypes.c_int]
@@ -153,3 +157,34 @@ def seg_attn_bwd(dout, q_seg, k_prefix, v_prefix, out, lse, seg_off: int, dq, dk
                               workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr())
     if rc != 0:
         raise S1FError(rc, "s1f_seg_attn_bwd")
+
+
+def seg_attn_bwd_dq(dout, q_seg, k_prefix, v_prefix, out, lse, seg_off: int, dq, workspace):
+    """s1f_seg_attn_bwd_dq: first half of the backward (dq, and delta into the workspace)."""
+    lib = load_library()
+    _same_layout(q_seg, dout, out, dq)
+    _same_layout(k_prefix, v_prefix)
+    desc = make_desc(q_seg, k_prefix)
+    rc = lib.s1f_seg_attn_bwd_dq(ctypes.byref(desc), dout.data_ptr(), q_seg.data_ptr(), k_prefix.data_ptr(),
+                                 v_prefix.data_ptr(), out.data_ptr(), lse.data_ptr(), int(seg_off),
+                                 int(q_seg.shape[2]), dq.data_ptr(), workspace.data_ptr(),
+                                 workspace.numel() * workspace.element_size(), _stream_ptr())
+    if rc != 0:
+        raise S1FError(rc, "s1f_seg_attn_bwd_dq")
+
+
+def seg_attn_bwd_dkdv(dout, q_seg, k_prefix, v_prefix, lse, seg_off: int, dk_prefix_acc, dv_prefix_acc, workspace):
+    """s1f_seg_attn_bwd_dkdv: second half of the backward (prefix dK/dV accumulation)."""
+    lib = load_library()
+    _same_layout(q_seg, dout)
+    _same_layout(k_prefix, v_prefix)
+    _same_layout(dk_prefix_acc, dv_prefix_acc)
+    if dk_prefix_acc.shape != k_prefix.shape or dk_prefix_acc.stride() != k_prefix.stride():
+        raise ValueError("gradient accumulators must have the shape and strides of k_prefix")
+    desc = make_desc(q_seg, k_prefix)
+    rc = lib.s1f_seg_attn_bwd_dkdv(ctypes.byref(desc), dout.data_ptr(), q_seg.data_ptr(), k_prefix.data_ptr(),
+                                   v_prefix.data_ptr(), lse.data_ptr(), int(seg_off), int(q_seg.shape[2]),
+                                   dk_prefix_acc.data_ptr(), dv_prefix_acc.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_ptr())
+    if rc != 0:
+        raise S1FError(rc, "s1f_seg_attn_bwd_dkdv")

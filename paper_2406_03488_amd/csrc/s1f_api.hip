@@ -68,19 +68,21 @@ template <typename T, int D> int fwd_impl(const s1f_desc *d, const AttnArgs &a, 
   return launch(seg_attn_fwd_kernel<T, D, S::NQ, S::BN>, grid, Cfg::LDS_BYTES, a, st);
 }
 
-template <typename T, int D> int bwd_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
+template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
   typedef Shape<T> S;
   typedef BwdDqCfg<T, D, S::NQ, S::BN> QC;
-  typedef BwdDkdvCfg<T, D, S::NK, S::BQ> KC;
   const dim3 gq((a.seg_len + QC::BM - 1) / QC::BM, d->n_q_heads, d->batch);
-  int rc = launch(seg_attn_bwd_dq_kernel<T, D, S::NQ, S::BN>, gq, QC::LDS_BYTES, a, st);
-  if (rc != S1F_OK) return rc;
+  return launch(seg_attn_bwd_dq_kernel<T, D, S::NQ, S::BN>, gq, QC::LDS_BYTES, a, st);
+}
+
+template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
+  typedef Shape<T> S;
+  typedef BwdDkdvCfg<T, D, S::NK, S::BQ> KC;
   const int kv_len = a.seg_off + a.seg_len;
   const dim3 gk((kv_len + KC::BNW - 1) / KC::BNW, d->n_kv_heads, d->batch);
   return launch(seg_attn_bwd_dkdv_kernel<T, D, S::NK, S::BQ>, gk, KC::LDS_BYTES, a, st);
 }
 
-template <template <typename, int> class F> struct Dispatch;
 
 #define S1F_DISPATCH(fn, d, ...)                                                        \
   do {                                                                                  \
@@ -121,27 +123,68 @@ extern "C" size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off,
   return (size_t)desc->batch * (size_t)desc->n_q_heads * (size_t)seg_len * sizeof(float);
 }
 
-extern "C" int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
-                                const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
-                                int64_t seg_len, void *dq, float *dk_prefix_acc, float *dv_prefix_acc,
-                                void *workspace, size_t workspace_bytes, void *hip_stream) {
+namespace {
+int bwd_dq_dispatch(const s1f_desc *d, const AttnArgs &a, hipStream_t st) { S1F_DISPATCH(bwd_dq_impl, d, d, a, st); }
+int bwd_dkdv_dispatch(const s1f_desc *d, const AttnArgs &a, hipStream_t st) { S1F_DISPATCH(bwd_dkdv_impl, d, d, a, st); }
+
+// Validation shared by the backward entry points; fills `a` on success.
+int bwd_prepare(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix, const void *v_prefix,
+                const float *lse, int64_t seg_off, int64_t seg_len, const void *workspace, size_t workspace_bytes,
+                AttnArgs *a) {
   int rc = check_desc(desc);
   if (rc != S1F_OK) return rc;
-  if (!dout || !q_seg || !k_prefix || !v_prefix || !out || !lse || !dq || !dk_prefix_acc || !dv_prefix_acc ||
-      !workspace)
-    return S1F_EINVAL;
-  if (!aligned16(dout) || !aligned16(q_seg) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(out) ||
-      !aligned16(dq) || !aligned16(dk_prefix_acc) || !aligned16(dv_prefix_acc) || !aligned16(workspace))
+  if (!dout || !q_seg || !k_prefix || !v_prefix || !lse || !workspace) return S1F_EINVAL;
+  if (!aligned16(dout) || !aligned16(q_seg) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(workspace))
     return S1F_EINVAL;
   rc = check_seg(desc, seg_off, seg_len);
   if (rc != S1F_OK) return rc;
   if (workspace_bytes < s1f_bwd_workspace_bytes(desc, seg_off, seg_len)) return S1F_EINVAL;
-  AttnArgs a = make_args(desc, seg_off, seg_len);
-  a.q = q_seg; a.k = k_prefix; a.v = v_prefix; a.out = out; a.dout = dout; a.dq = dq;
-  a.lse = const_cast<float *>(lse); a.delta = reinterpret_cast<float *>(workspace);
+  *a = make_args(desc, seg_off, seg_len);
+  a->q = q_seg; a->k = k_prefix; a->v = v_prefix; a->dout = dout;
+  a->lse = const_cast<float *>(lse);
+  a->delta = reinterpret_cast<float *>(const_cast<void *>(workspace));
+  return S1F_OK;
+}
+}  // namespace
+
+extern "C" int s1f_seg_attn_bwd_dq(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
+                                   const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
+                                   int64_t seg_len, void *dq, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream) {
+  AttnArgs a;
+  const int rc = bwd_prepare(desc, dout, q_seg, k_prefix, v_prefix, lse, seg_off, seg_len, workspace, workspace_bytes, &a);
+  if (rc != S1F_OK) return rc;
+  if (!out || !dq || !aligned16(out) || !aligned16(dq)) return S1F_EINVAL;
+  a.out = out; a.dq = dq;
+  return bwd_dq_dispatch(desc, a, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int s1f_seg_attn_bwd_dkdv(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
+                                     const void *v_prefix, const float *lse, int64_t seg_off, int64_t seg_len,
+                                     float *dk_prefix_acc, float *dv_prefix_acc, const void *workspace,
+                                     size_t workspace_bytes, void *hip_stream) {
+  AttnArgs a;
+  const int rc = bwd_prepare(desc, dout, q_seg, k_prefix, v_prefix, lse, seg_off, seg_len, workspace, workspace_bytes, &a);
+  if (rc != S1F_OK) return rc;
+  if (!dk_prefix_acc || !dv_prefix_acc || !aligned16(dk_prefix_acc) || !aligned16(dv_prefix_acc)) return S1F_EINVAL;
   a.dk_acc = dk_prefix_acc; a.dv_acc = dv_prefix_acc;
+  return bwd_dkdv_dispatch(desc, a, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
+                                const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
+                                int64_t seg_len, void *dq, float *dk_prefix_acc, float *dv_prefix_acc,
+                                void *workspace, size_t workspace_bytes, void *hip_stream) {
+  AttnArgs a;
+  const int rc = bwd_prepare(desc, dout, q_seg, k_prefix, v_prefix, lse, seg_off, seg_len, workspace, workspace_bytes, &a);
+  if (rc != S1F_OK) return rc;
+  if (!out || !dq || !dk_prefix_acc || !dv_prefix_acc) return S1F_EINVAL;
+  if (!aligned16(out) || !aligned16(dq) || !aligned16(dk_prefix_acc) || !aligned16(dv_prefix_acc)) return S1F_EINVAL;
+  a.out = out; a.dq = dq; a.dk_acc = dk_prefix_acc; a.dv_acc = dv_prefix_acc;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  S1F_DISPATCH(bwd_impl, desc, desc, a, st);
+  const int rq = bwd_dq_dispatch(desc, a, st);
+  if (rq != S1F_OK) return rq;
+  return bwd_dkdv_dispatch(desc, a, st);
 }
 
 extern "C" const char *s1f_strerror(int status) {
