@@ -25,8 +25,8 @@ template <typename T, int D, int NQ, int BN> struct BwdDqCfg {
 //   S^T[key][q]  = K Q^T      A = K (LDS),            B = Q (registers)
 //   dP^T[key][q] = V dO^T     A = V (LDS),            B = dO (registers)
 //   dQ^T[d][q]  += K^T dS^T   A = K read transposed,  B = dS^T slab (registers)
-template <typename T, int D, int NQ, int BN>
-__global__ void __launch_bounds__(256) seg_attn_bwd_dq_kernel(const AttnArgs a) {
+template <typename T, int D, int NQ, int BN, int OCC>
+__global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArgs a) {
   typedef Elem<T> E;
   typedef typename E::Frag Frag;
   typedef LdsTile<T, BN, D> KT;
@@ -63,7 +63,7 @@ __global__ void __launch_bounds__(256) seg_attn_bwd_dq_kernel(const AttnArgs a) 
       dof[nq][ks] = load_frag_global<T>(dob + off + ks * KSTEP);
       part += frag_dot<T>(dof[nq][ks], load_frag_global<T>(ob + off + ks * KSTEP));
     }
-    delta[nq] = part + xor32(part);
+    delta[nq] = sum_xor32(part);
     lse2[nq] = a.lse[lse_off + rc] * kLog2e;
     if (r < seg_len && g == 0) a.delta[lse_off + r] = delta[nq];
   }

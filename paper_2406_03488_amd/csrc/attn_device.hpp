@@ -48,7 +48,27 @@ S1F_DEV f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) { return __builtin_amdgcn_mfma_
 S1F_DEV f32x16 mma(float a, float b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
 
 S1F_DEV float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
-S1F_DEV float xor32(float x) { return __shfl_xor(x, 32, 64); }            // partner lane of the other half-wave
+// The lane's own value and the value held by its partner lane (lane ^ 32), in unspecified order.
+// v_permlane32_swap exchanges the upper half of its first operand with the lower half of its second, so
+// with both operands equal to x the register pair ends up as (own, partner) in the lower half-wave and
+// (partner, own) in the upper one.  Written as assembly: with two identical operands the compiler's
+// builtin hands back its first result for both.  The leading s_nop covers the wait states the
+// instruction needs after a vector write of its operands.
+S1F_DEV void own_and_partner(float x, float &a, float &b) {
+  a = x;
+  b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+S1F_DEV float max_xor32(float x) {
+  float a, b;
+  own_and_partner(x, a, b);
+  return fmaxf(a, b);
+}
+S1F_DEV float sum_xor32(float x) {
+  float a, b;
+  own_and_partner(x, a, b);
+  return a + b;
+}
 
 template <typename T> S1F_DEV typename Elem<T>::Frag load_frag_global(const T *p);
 template <> S1F_DEV float load_frag_global<float>(const float *p) { return *p; }
@@ -151,6 +171,52 @@ S1F_DEV typename Elem<T>::Frag LdsTile<T, ROWS, D>::tr_frag(const char *tile, in
   return TileOps<LdsTile<T, ROWS, D>>::tr(tile, row32, t, db, lane);
 }
 
+// Lane-resident byte offsets for reading operand fragments of 32-row blocks out of an LdsTile.  The
+// swizzle depends on the row modulo 16 only, so for a block starting at a multiple of 16 rows every
+// address is (block base: uniform) + (lane part: computed once, here) [+ a compile-time slab offset].
+// `block` below is tile + first_row_of_block * ROW_BYTES.
+template <typename TL, typename T> struct FragReader;
+
+template <int ROWS, int D> struct FragReader<LdsTile<bf16_t, ROWS, D>, bf16_t> {
+  typedef LdsTile<bf16_t, ROWS, D> TL;
+  static constexpr int NKS = D / 16, DB = TL::DPAD / 32;
+  static constexpr int ROW_BYTES = TL::RS * 16;
+  int nat_off[NKS];
+  int tr_off[DB][2];
+  S1F_DEV void init(int lane) {
+    const int g = lane >> 5, ln = lane & 31, i = lane & 15, b = lane >> 4;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) nat_off[ks] = TL::chunk_off(ln, 2 * ks + g);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const int c = 4 * db + 2 * (b & 1) + ((i & 3) >> 1);
+      const int r0 = 4 * g + (i >> 2);
+      tr_off[db][0] = TL::chunk_off(r0, c) + (i & 1) * 8;
+      tr_off[db][1] = TL::chunk_off(r0 + 8, c) + (i & 1) * 8;
+    }
+  }
+  // contraction along D: row ln of the block, elements [16 ks + 8 g, +8)
+  S1F_DEV bf16x8 nat(const char *block, int ks) const { return *reinterpret_cast<const bf16x8 *>(block + nat_off[ks]); }
+  // contraction along the block's rows (slab t), operand index d = 32 db + ln; see TileOps::tr
+  S1F_DEV bf16x8 tr(const char *block, int t, int db) const {
+    const char *p = block + t * 16 * ROW_BYTES;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(S1F_LDS(s16x4, p + tr_off[db][0]));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(S1F_LDS(s16x4, p + tr_off[db][1]));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+  }
+};
+
+template <int ROWS, int D> struct FragReader<LdsTile<float, ROWS, D>, float> {
+  typedef LdsTile<float, ROWS, D> TL;
+  static constexpr int ROW_BYTES = TL::RS * 16;
+  int lane_;
+  S1F_DEV void init(int lane) { lane_ = lane; }
+  S1F_DEV float nat(const char *block, int ks) const { return TL::nat_frag(block, lane_ & 31, ks, lane_ >> 5); }
+  S1F_DEV float tr(const char *block, int t, int db) const { return TL::tr_frag(block, 0, t, db, lane_); }
+};
+
 // Register-staged copy of a [ROWS x D] tile from global memory (row stride in elements) into an
 // LdsTile, by NT threads, 16 bytes per access.  Rows >= rows_valid are filled with zeros.
 template <typename T, int ROWS, int D, int NT> struct TileCopy {
@@ -160,14 +226,24 @@ template <typename T, int ROWS, int D, int NT> struct TileCopy {
   u32x4 regs[PER];
 
   S1F_DEV void load(const T *base, int64_t row_stride, int rows_valid, int tid) {
+    if (rows_valid >= ROWS) {   // whole tile in range (the common case): no per-row predicate
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int id = tid + i * NT;
-      const int r = id / TL::CPR, c = id % TL::CPR;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if ((TOTAL % NT == 0 || id < TOTAL) && r < rows_valid)
-        v = *reinterpret_cast<const u32x4 *>(base + (int64_t)r * row_stride + c * TL::CE);
-      regs[i] = v;
+      for (int i = 0; i < PER; ++i) {
+        const int id = tid + i * NT;
+        const int r = id / TL::CPR, c = id % TL::CPR;
+        if (TOTAL % NT == 0 || id < TOTAL)
+          regs[i] = *reinterpret_cast<const u32x4 *>(base + (int64_t)r * row_stride + c * TL::CE);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int id = tid + i * NT;
+        const int r = id / TL::CPR, c = id % TL::CPR;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if ((TOTAL % NT == 0 || id < TOTAL) && r < rows_valid)
+          v = *reinterpret_cast<const u32x4 *>(base + (int64_t)r * row_stride + c * TL::CE);
+        regs[i] = v;
+      }
     }
   }
   S1F_DEV void store(char *tile, int tid) const {
@@ -179,6 +255,49 @@ template <typename T, int ROWS, int D, int NT> struct TileCopy {
     }
   }
 };
+
+// Asynchronous copy of a [ROWS x D] tile from global memory straight into an LdsTile (no register
+// staging) by the NW waves of a workgroup.  One global_load_lds_dwordx4 moves 16 bytes per lane into 1 KiB
+// of consecutive LDS (lane l lands at base + 16*l), so the instruction that fills 16-byte slots
+// [64*n, 64*n+64) of the tile makes lane l fetch the chunk that the swizzle places in slot 64*n + l.
+// Rows past `rows_total` re-read the last valid row (callers mask them); slots of padding columns
+// (head_dim 80) re-read a valid chunk of the same row.  Completion is tracked by the wave's vmcnt.
+template <typename T, int ROWS, int D, int NW> struct AsyncTile {
+  typedef LdsTile<T, ROWS, D> TL;
+  static constexpr int SLOTS = ROWS * TL::RS;
+  static constexpr int PER = SLOTS / (64 * NW);     // instructions per wave
+  static_assert(SLOTS % (64 * NW) == 0, "tile must split evenly over the workgroup's waves");
+  int row[PER];     // tile row fetched by this lane in instruction i
+  int coff[PER];    // element offset of its chunk inside the row
+
+  S1F_DEV void init(int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int slot = (wave * PER + i) * 64 + lane;
+      const int r = slot / TL::RS, pos = slot % TL::RS;
+      int c = pos ^ TL::swz(r);
+      if (TL::CPR < TL::RS && c >= TL::CPR) c &= TL::RS / 2 - 1;
+      row[i] = r;
+      coff[i] = c * TL::CE;
+    }
+  }
+  S1F_DEV void issue(const T *base, int64_t row_stride, int tile_row0, int rows_total, char *tile, int wave) const {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      int r = tile_row0 + row[i];
+      r = r < rows_total ? r : rows_total - 1;
+      const T *p = base + (int64_t)r * row_stride + coff[i];
+      // Written as assembly so that the compiler's wait-count pass does not tie later LDS reads of OTHER
+      // ring stages to this copy (it would wait for it before the first LDS read); the callers order the
+      // copy against its readers with wait_async_tiles() + a workgroup barrier.
+      const unsigned dst = (unsigned)(uintptr_t)S1F_LDS(char, tile) + (unsigned)((wave * PER + i) * 1024);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(p) : "m0");
+    }
+  }
+};
+
+// Wait until every asynchronous tile copy issued by this wave has landed (vmcnt(0), other counters untouched).
+S1F_DEV void wait_async_tiles() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Store 4 consecutive head_dim elements of one row.
 template <typename T> S1F_DEV void store4(T *p, float a, float b, float c, float d);

@@ -1,37 +1,166 @@
 // Forward of one segment: out = softmax(q k^T / sqrt(D), causal with the diagonal shifted by seg_off) v,
 // lse = log-sum-exp of the scaled scores (Section 3.1, Eq. 3, restricted to the segment's rows).
 //
-// One workgroup (4 waves) owns BM = 128*NQ query rows of one head; wave w owns rows 32*NQ*w .. +32*NQ.
+// One workgroup (NW waves) owns BM = 32*NQ*NW query rows of one head; wave w owns rows 32*NQ*w .. +32*NQ.
 // The transposed products are computed so that a lane always holds ONE query (column ln) and the
 // keys run over registers:
 //     S^T[key][q] = sum_d K[key][d] Q[q][d]        A = K fragment from LDS, B = Q fragment (registers)
 //     O^T[d][q]  += sum_key V[key][d] P^T[key][q]  A = V read transposed from LDS, B = P^T slab (registers)
 // Row maximum and sum are then in-lane reductions plus one exchange with the partner lane (lane ^ 32).
-// K/V tiles of BN keys are staged through registers into double-buffered, swizzled LDS tiles.
-// Key tiles wholly above the shifted diagonal are never visited; tiles wholly below it skip masking.
+//
+// K/V tiles of BN = 32*KB keys go from HBM straight into a 3-stage ring of swizzled LDS tiles (no register
+// staging); tile j+2 is in flight while tiles j and j+1 are consumed, with one workgroup barrier per tile.
+// The loop advances in steps of one 32-key block and is software-pipelined inside each wave: the score
+// product of block k+1 (matrix pipe) is issued together with the exponentials of block k (vector pipe),
+// then the PV product of block k follows.  Key blocks wholly above the shifted diagonal are never
+// visited; blocks wholly below it run a step without any masking code.
 #pragma once
 #include "attn_device.hpp"
 
 namespace s1f {
 
-template <typename T, int D, int NQ, int BN> struct FwdCfg {
-  static constexpr int BM = 128 * NQ;
+// Lazy rescaling: the running maximum m of a row is only raised when the new block's maximum exceeds it by
+// more than kRescaleTau (in log2 units).  Probabilities are then at most 2^kRescaleTau instead of 1, which
+// fp32 sums and bf16 operands hold without loss, and the accumulator rescale (a pass over every O
+// register) leaves the steady-state loop: it runs only when some row of the wave needs it.
+constexpr float kRescaleTau = 8.0f;
+
+template <typename T, int D, int NQ, int KB, int NW> struct FwdCfg {
+  static constexpr int BM = 32 * NQ * NW;
+  static constexpr int BN = 32 * KB;
+  static constexpr int THREADS = 64 * NW;
   typedef LdsTile<T, BN, D> KT;
-  static constexpr int LDS_BYTES = 4 * KT::BYTES;   // {K, V} x 2 buffers
+  static constexpr int STAGE_BYTES = 2 * KT::BYTES;      // K tile then V tile
+  static constexpr int LDS_BYTES = 3 * STAGE_BYTES;
 };
 
-template <typename T, int D, int NQ, int BN>
-__global__ void __launch_bounds__(256) seg_attn_fwd_kernel(const AttnArgs a) {
+// Number of operand fragments a wave keeps in flight ahead of the matrix instruction that consumes them
+// (LDS latency is about three 32x32x16 MFMAs).
+constexpr int kPrefetch = 3;
+
+// S^T blocks of one 32-key block: s[nq] = K[block rows, :] Q^T   (prologue only; the loop uses fwd_step)
+template <typename RD, typename T, int NQ, int NKS>
+S1F_DEV void fwd_scores(f32x16 (&s)[NQ], const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd, const char *kblock) {
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[nq][v] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) {
+    const typename Elem<T>::Frag kf = rd.nat(kblock, ks);
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) s[nq] = mma(kf, qf[nq][ks], s[nq]);
+  }
+}
+
+// Masks the scores of a block that crosses the diagonal.
+//   lim0 = (absolute row of this lane's query in query block 0) - (first key of the block) - 4g
+template <int NQ> S1F_DEV void fwd_mask(f32x16 (&s)[NQ], int lim0) {
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    const int lim = lim0 + 32 * nq;   // register v is visible iff 8*(v/4) + v%4 <= lim
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[nq][v] = (8 * (v >> 2) + (v & 3) > lim) ? -INFINITY : s[nq][v];
+  }
+}
+
+// Row maxima of a block in log2 units (each lane gets the maximum of its query's 32 scores).
+template <int NQ> S1F_DEV void fwd_row_max(const f32x16 (&s)[NQ], float (&mx)[NQ], float c) {
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    float x = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) x = fmaxf(x, s[nq][v]);
+    mx[nq] = max_xor32(x) * c;
+  }
+}
+
+// One pipelined step over block k, whose scores are in `s` with m already covering them:
+//   phase 1   sn = scores of block k+1 (matrix pipe)  ||  p = exp2(s*c - m), row sums (vector pipe)
+//   phase 2   O += P V of block k (matrix pipe)
+// Operand fragments are read from LDS kPrefetch matrix instructions ahead of their use; the scheduling
+// fences keep that order in the generated code.
+template <typename RD, typename T, bool HAS_NEXT, int NQ, int NKS, int DB>
+S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], const float (&m)[NQ], float (&l)[NQ],
+                      const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd, const char *kblock_next,
+                      const char *vblock, float c) {
+  typedef typename Elem<T>::Frag Frag;
+  constexpr int NSLAB = 16 / Elem<T>::EPL;
+  constexpr int PF = kPrefetch;
+
+  float rs[NQ];
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) rs[nq] = 0.f;
+  if (HAS_NEXT) {
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sn[nq][v] = 0.f;
+    Frag kf[PF];
+#pragma unroll
+    for (int i = 0; i < PF && i < NKS; ++i) kf[i] = rd.nat(kblock_next, i);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) sn[nq] = mma(kf[ks % PF], qf[nq][ks], sn[nq]);
+      if (ks + PF < NKS) kf[ks % PF] = rd.nat(kblock_next, ks + PF);
+      // this slot's share of the 16 exponentials per query block
+#pragma unroll
+      for (int v = 16 * ks / NKS; v < 16 * (ks + 1) / NKS; ++v)
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+          const float p = exp2_fast(fmaf(s[nq][v], c, -m[nq]));
+          s[nq][v] = p;
+          rs[nq] += p;
+        }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = exp2_fast(fmaf(s[nq][v], c, -m[nq]));
+        s[nq][v] = p;
+        rs[nq] += p;
+      }
+  }
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) l[nq] += rs[nq];
+
+  constexpr int NV = NSLAB * DB;   // V fragments of the block, in the order (slab, d-block)
+  Frag vf[PF];
+#pragma unroll
+  for (int i = 0; i < PF && i < NV; ++i) vf[i] = rd.tr(vblock, i / DB, i % DB);
+#pragma unroll
+  for (int t = 0; t < NSLAB; ++t) {
+    Frag pf[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) pf[nq] = block_slab<T>(s[nq], t);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const int i = t * DB + db;
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) o[nq][db] = mma(vf[i % PF], pf[nq], o[nq][db]);
+      if (i + PF < NV) vf[i % PF] = rd.tr(vblock, (i + PF) / DB, (i + PF) % DB);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+template <typename T, int D, int NQ, int KB, int NW, int OCC>
+__global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnArgs a) {
   typedef Elem<T> E;
   typedef typename E::Frag Frag;
-  typedef LdsTile<T, BN, D> KT;
+  typedef FwdCfg<T, D, NQ, KB, NW> Cfg;
+  typedef typename Cfg::KT KT;
   constexpr int EPL = E::EPL, KSTEP = 2 * EPL, NKS = D / KSTEP;
-  constexpr int DB = KT::DPAD / 32, NSLAB = 16 / EPL, KB = BN / 32;
-  constexpr int BM = 128 * NQ;
-  static_assert(D % KSTEP == 0 && BN % 32 == 0, "shape");
+  constexpr int DB = KT::DPAD / 32, BM = Cfg::BM, BN = Cfg::BN;
+  static_assert(D % KSTEP == 0, "shape");
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;   // later (heavier) row tiles are scheduled first
   const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
   const int seg_off = a.seg_off, seg_len = a.seg_len, kv_len = seg_off + seg_len;
@@ -40,6 +169,20 @@ __global__ void __launch_bounds__(256) seg_attn_fwd_kernel(const AttnArgs a) {
   const T *qb = reinterpret_cast<const T *>(a.q) + b * a.q_sb + h * a.q_sh;
   const T *kbase = reinterpret_cast<const T *>(a.k) + b * a.kv_sb + hk * a.kv_sh;
   const T *vbase = reinterpret_cast<const T *>(a.v) + b * a.kv_sb + hk * a.kv_sh;
+
+  const int last_row = (row0 + BM < seg_len ? row0 + BM : seg_len) - 1;
+  const int n_blk = (seg_off + last_row) / 32 + 1;           // 32-key blocks holding keys 0 .. seg_off+last_row
+  const int n_kt = (n_blk + KB - 1) / KB;
+
+  AsyncTile<T, BN, D, NW> ld;
+  ld.init(wave, lane);
+  auto issue = [&](int jt) {
+    char *st = smem + (jt % 3) * Cfg::STAGE_BYTES;
+    ld.issue(kbase, a.kv_ss, jt * BN, kv_len, st, wave);
+    ld.issue(vbase, a.kv_ss, jt * BN, kv_len, st + KT::BYTES, wave);
+  };
+  issue(0);
+  if (n_kt > 1) issue(1);
 
   Frag qf[NQ][NKS];
 #pragma unroll
@@ -62,109 +205,72 @@ __global__ void __launch_bounds__(256) seg_attn_fwd_kernel(const AttnArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) o[nq][db][v] = 0.f;
   }
-
-  const int last_row = (row0 + BM < seg_len ? row0 + BM : seg_len) - 1;
-  const int n_kt = (seg_off + last_row) / BN + 1;            // tiles holding keys 0 .. seg_off+last_row
-  const bool w_active = wrow0 < seg_len;
-  const int w_last = (wrow0 + 32 * NQ < seg_len ? wrow0 + 32 * NQ : seg_len) - 1;
   const float c = a.scale * kLog2e;
 
-  TileCopy<T, BN, D, 256> ck, cv;
-  ck.load(kbase, a.kv_ss, kv_len, tid);
-  cv.load(vbase, a.kv_ss, kv_len, tid);
-  ck.store(smem, tid);
-  cv.store(smem + KT::BYTES, tid);
-  __syncthreads();
+  FragReader<KT, T> rd;
+  rd.init(lane);
+  constexpr int BLOCK_BYTES = 32 * KT::RS * 16;
 
-  for (int jt = 0; jt < n_kt; ++jt) {
-    const char *kt = smem + (jt & 1) * 2 * KT::BYTES;
-    const char *vt = kt + KT::BYTES;
-    const int key0 = jt * BN;
-    if (jt + 1 < n_kt) {
-      const int nk0 = key0 + BN;
-      ck.load(kbase + (int64_t)nk0 * a.kv_ss, a.kv_ss, kv_len - nk0, tid);
-      cv.load(vbase + (int64_t)nk0 * a.kv_ss, a.kv_ss, kv_len - nk0, tid);
-    }
-    if (w_active && key0 <= seg_off + w_last) {
-      f32x16 s[KB][NQ];
+  wait_async_tiles();
+  __syncthreads();
+  f32x16 s[NQ], sn[NQ];
+  float mx[NQ];
+  fwd_scores<FragReader<KT, T>, T, NQ, NKS>(s, qf, rd, smem);
+  if (31 > seg_off + wrow0) fwd_mask(s, seg_off + wrow0 + ln - 4 * g);
+  fwd_row_max(s, mx, c);
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) s[kb][nq][v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-          const Frag kf = KT::nat_frag(kt, 32 * kb + ln, ks, g);
-#pragma unroll
-          for (int nq = 0; nq < NQ; ++nq) s[kb][nq] = mma(kf, qf[nq][ks], s[kb][nq]);
-        }
+  for (int nq = 0; nq < NQ; ++nq) m[nq] = mx[nq];   // key 0 is visible to every row: finite
+
+  // The steady loop never touches O except through the matrix pipe.  When some row of the wave has to
+  // raise its running maximum the loop is left, O and l are rescaled, and the loop is entered again.
+  int k = 0;
+  while (true) {
+    bool raise_any = false;
+    while (k + 1 < n_blk) {
+      const int jt = k / KB, kb = k % KB;
+      if (kb == KB - 1) {
+        wait_async_tiles();   // this wave's part of tile jt+1 has landed (it was issued a whole tile ago)
+        __syncthreads();      // ... and everyone's; every wave has also finished reading tile jt-1
+        if (jt + 2 < n_kt) issue(jt + 2);
       }
-      if (key0 + BN - 1 > seg_off + wrow0) {   // the tile crosses the diagonal for some row of this wave
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int nq = 0; nq < NQ; ++nq) {
-            const int lim = seg_off + wrow0 + 32 * nq + ln - (key0 + 32 * kb + 4 * g);   // visible iff 8*(v/4)+v%4 <= lim
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-              if (8 * (v >> 2) + (v & 3) > lim) s[kb][nq][v] = -INFINITY;
-          }
-      }
+      const char *vblock = smem + (jt % 3) * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
+      const int kn = k + 1;
+      const char *kblock_next = smem + ((kn / KB) % 3) * Cfg::STAGE_BYTES + (kn % KB) * BLOCK_BYTES;
+      fwd_step<FragReader<KT, T>, T, true>(s, sn, o, m, l, qf, rd, kblock_next, vblock, c);
+      // the last block always crosses the diagonal; earlier ones do if their last key is past the wave's first row
+      if (kn + 1 == n_blk || 32 * kn + 31 > seg_off + wrow0) fwd_mask(sn, seg_off + wrow0 + ln - 32 * kn - 4 * g);
+      fwd_row_max(sn, mx, c);
+      bool raise = false;
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][nq][v]);
-        mx = fmaxf(mx, xor32(mx));
-        const float m_new = fmaxf(m[nq], mx * c);
-        const float alpha = exp2_fast(m[nq] - m_new);
-        m[nq] = m_new;
-        float rs = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float p = exp2_fast(fmaf(s[kb][nq][v], c, -m_new));
-            s[kb][nq][v] = p;
-            rs += p;
-          }
-        l[nq] = l[nq] * alpha + rs;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) o[nq][db][v] *= alpha;
+        s[nq] = sn[nq];
+        raise = raise || (mx[nq] > m[nq] + kRescaleTau);
       }
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int t = 0; t < NSLAB; ++t) {
-          Frag pf[NQ];
-#pragma unroll
-          for (int nq = 0; nq < NQ; ++nq) pf[nq] = block_slab<T>(s[kb][nq], t);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            const Frag vf = KT::tr_frag(vt, 32 * kb, t, db, lane);
-#pragma unroll
-            for (int nq = 0; nq < NQ; ++nq) o[nq][db] = mma(vf, pf[nq], o[nq][db]);
-          }
-        }
+      k = kn;
+      if (__builtin_amdgcn_ballot_w64(raise) != 0) { raise_any = true; break; }
     }
-    if (jt + 1 < n_kt) {
-      char *nk = smem + ((jt + 1) & 1) * 2 * KT::BYTES;
-      ck.store(nk, tid);
-      cv.store(nk + KT::BYTES, tid);
+    if (!raise_any) break;
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+      const float m_up = mx[nq] > m[nq] + kRescaleTau ? mx[nq] : m[nq];
+      const float alpha = exp2_fast(m[nq] - m_up);   // exactly 1 for rows that keep their maximum
+      m[nq] = m_up;
+      l[nq] *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) o[nq][db] = o[nq][db] * alpha;
     }
-    __syncthreads();
+  }
+  {   // last block: no next scores to compute
+    const int jt = k / KB, kb = k % KB;
+    const char *vblock = smem + (jt % 3) * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
+    fwd_step<FragReader<KT, T>, T, false>(s, sn, o, m, l, qf, rd, vblock, vblock, c);
   }
 
   T *ob = reinterpret_cast<T *>(a.out_w) + b * a.q_sb + h * a.q_sh;
   float *lse = a.lse + ((int64_t)b * a.n_q_heads + h) * seg_len;
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
-    const float lt = l[nq] + xor32(l[nq]);
+    const float lt = sum_xor32(l[nq]);
     const float inv = 1.f / lt;
     const int r = wrow0 + 32 * nq + ln;
     if (r < seg_len) {

@@ -14,8 +14,8 @@ using namespace s1f;
 // Tile shapes per element type: query blocks per wave (NQ), key blocks per wave (NK), keys per staged
 // K/V tile (BN), rows per staged Q/dO tile (BQ).
 template <typename T> struct Shape;
-template <> struct Shape<bf16_t> { static constexpr int NQ = 2, BN = 64, NK = 1, BQ = 64; };
-template <> struct Shape<float>  { static constexpr int NQ = 1, BN = 32, NK = 1, BQ = 32; };
+template <> struct Shape<bf16_t> { static constexpr int NQ = 1, KB = 2, NW = 8, BN = 64, OCC = 2, NK = 1, BQ = 64; };
+template <> struct Shape<float>  { static constexpr int NQ = 1, KB = 1, NW = 4, BN = 32, OCC = 1, NK = 1, BQ = 32; };
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -51,28 +51,28 @@ AttnArgs make_args(const s1f_desc *d, int64_t seg_off, int64_t seg_len) {
   return a;
 }
 
-template <typename K> int launch(K kernel, dim3 grid, int lds_bytes, const AttnArgs &a, hipStream_t st) {
+template <typename K> int launch(K kernel, dim3 grid, int threads, int lds_bytes, const AttnArgs &a, hipStream_t st) {
   if (lds_bytes > 64 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                             lds_bytes) != hipSuccess)
       return S1F_EDEVICE;
   }
-  hipLaunchKernelGGL(kernel, grid, dim3(256), lds_bytes, st, a);
+  hipLaunchKernelGGL(kernel, grid, dim3(threads), lds_bytes, st, a);
   return hipGetLastError() == hipSuccess ? S1F_OK : S1F_EDEVICE;
 }
 
 template <typename T, int D> int fwd_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
   typedef Shape<T> S;
-  typedef FwdCfg<T, D, S::NQ, S::BN> Cfg;
+  typedef FwdCfg<T, D, S::NQ, S::KB, S::NW> Cfg;
   const dim3 grid((a.seg_len + Cfg::BM - 1) / Cfg::BM, d->n_q_heads, d->batch);
-  return launch(seg_attn_fwd_kernel<T, D, S::NQ, S::BN>, grid, Cfg::LDS_BYTES, a, st);
+  return launch(seg_attn_fwd_kernel<T, D, S::NQ, S::KB, S::NW, S::OCC>, grid, Cfg::THREADS, Cfg::LDS_BYTES, a, st);
 }
 
 template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
   typedef Shape<T> S;
   typedef BwdDqCfg<T, D, S::NQ, S::BN> QC;
   const dim3 gq((a.seg_len + QC::BM - 1) / QC::BM, d->n_q_heads, d->batch);
-  return launch(seg_attn_bwd_dq_kernel<T, D, S::NQ, S::BN>, gq, QC::LDS_BYTES, a, st);
+  return launch(seg_attn_bwd_dq_kernel<T, D, S::NQ, S::BN, S::OCC>, gq, 256, QC::LDS_BYTES, a, st);
 }
 
 template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
@@ -80,7 +80,7 @@ template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs
   typedef BwdDkdvCfg<T, D, S::NK, S::BQ> KC;
   const int kv_len = a.seg_off + a.seg_len;
   const dim3 gk((kv_len + KC::BNW - 1) / KC::BNW, d->n_kv_heads, d->batch);
-  return launch(seg_attn_bwd_dkdv_kernel<T, D, S::NK, S::BQ>, gk, KC::LDS_BYTES, a, st);
+  return launch(seg_attn_bwd_dkdv_kernel<T, D, S::NK, S::BQ>, gk, 256, KC::LDS_BYTES, a, st);
 }
 
 
