@@ -36,8 +36,10 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
-  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
+  int qt, bh;
+  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, qt, bh);
+  qt = a.n_tiles - 1 - qt;   // later (heavier) row tiles are scheduled first
+  const int h = bh % a.n_q_heads, b = bh / a.n_q_heads, hk = h / a.group;
   const int seg_off = a.seg_off, seg_len = a.seg_len, kv_len = seg_off + seg_len;
   const int row0 = qt * BM, wrow0 = row0 + wave * 32 * NQ;
 
@@ -193,9 +195,12 @@ __global__ void __launch_bounds__(256) seg_attn_bwd_dkdv_kernel(const AttnArgs a
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
-  const int hk = blockIdx.y, b = blockIdx.z;
+  int kt, bh;
+  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, kt, bh);   // early key tiles see every query row: heaviest first
+  const int n_kv_heads = a.n_q_heads / a.group;
+  const int hk = bh % n_kv_heads, b = bh / n_kv_heads;
   const int seg_off = a.seg_off, seg_len = a.seg_len, kv_len = seg_off + seg_len;
-  const int j0 = blockIdx.x * Cfg::BNW;            // first key of the workgroup
+  const int j0 = kt * Cfg::BNW;                    // first key of the workgroup
   const int wkey0 = j0 + wave * 32 * NK;           // first key of the wave
 
   const int64_t kvoff = b * a.kv_sb + hk * a.kv_sh;

@@ -171,37 +171,72 @@ S1F_DEV typename Elem<T>::Frag LdsTile<T, ROWS, D>::tr_frag(const char *tile, in
   return TileOps<LdsTile<T, ROWS, D>>::tr(tile, row32, t, db, lane);
 }
 
-// Lane-resident byte offsets for reading operand fragments of 32-row blocks out of an LdsTile.  The
-// swizzle depends on the row modulo 16 only, so for a block starting at a multiple of 16 rows every
-// address is (block base: uniform) + (lane part: computed once, here) [+ a compile-time slab offset].
-// `block` below is tile + first_row_of_block * ROW_BYTES.
+// LDS addresses are handled as 32-bit byte offsets (lds_addr) so that address arithmetic, including the
+// XOR of the swizzle, stays in the LDS address space.
+typedef unsigned lds_addr;
+S1F_DEV lds_addr to_lds_addr(const void *p) { return (lds_addr)(uintptr_t)S1F_LDS(const char, p); }
+template <typename V> S1F_DEV V lds_load(lds_addr a) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) V *>((uintptr_t)a);
+}
+S1F_DEV const char *lds_generic(lds_addr a) {
+  return (const char *)reinterpret_cast<const __attribute__((address_space(3))) char *>((uintptr_t)a);
+}
+
+// Reads operand fragments of 32-row blocks out of an LdsTile.  The swizzle depends on the row modulo 16
+// only, so for a block starting at a multiple of 16 rows every address is (block base: uniform) combined
+// with a lane part computed once, here.  `block` below is the LDS address of the block's first row.
 template <typename TL, typename T> struct FragReader;
 
 template <int ROWS, int D> struct FragReader<LdsTile<bf16_t, ROWS, D>, bf16_t> {
   typedef LdsTile<bf16_t, ROWS, D> TL;
   static constexpr int NKS = D / 16, DB = TL::DPAD / 32;
   static constexpr int ROW_BYTES = TL::RS * 16;
-  int nat_off[NKS];
-  int tr_off[DB][2];
+  // With 256-byte rows (RS == 16) the swizzle is an XOR on address bits 4..7 that no other term touches,
+  // so one lane value per access pattern is enough: fragment ks / d-block db is reached by XOR-ing a
+  // compile-time constant into it.  `block` must then be aligned to 8 KiB (the kernels' LDS bases are).
+  // Shorter rows keep one precomputed offset per fragment.
+  static constexpr bool XOR_FORM = TL::RS == 16;
+  unsigned nat_x, tr_x;
+  unsigned nat_off[XOR_FORM ? 1 : NKS];
+  unsigned tr_off[XOR_FORM ? 1 : DB][2];
   S1F_DEV void init(int lane) {
     const int g = lane >> 5, ln = lane & 31, i = lane & 15, b = lane >> 4;
+    const int r0 = 4 * g + (i >> 2), cl = 2 * (b & 1) + ((i & 3) >> 1);
+    nat_x = TL::chunk_off(ln, g);                    // fragment ks: nat_x ^ (32 * ks)
+    tr_x = TL::chunk_off(r0, cl) + (i & 1) * 8;      // d-block db, row half hh: tr_x ^ (64 * db) ^ (hh * (32 + 2048))
+    if (!XOR_FORM) {
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) nat_off[ks] = TL::chunk_off(ln, 2 * ks + g);
+      for (int ks = 0; ks < NKS; ++ks) nat_off[ks] = TL::chunk_off(ln, 2 * ks + g);
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      const int c = 4 * db + 2 * (b & 1) + ((i & 3) >> 1);
-      const int r0 = 4 * g + (i >> 2);
-      tr_off[db][0] = TL::chunk_off(r0, c) + (i & 1) * 8;
-      tr_off[db][1] = TL::chunk_off(r0 + 8, c) + (i & 1) * 8;
+      for (int db = 0; db < DB; ++db) {
+        tr_off[db][0] = TL::chunk_off(r0, 4 * db + cl) + (i & 1) * 8;
+        tr_off[db][1] = TL::chunk_off(r0 + 8, 4 * db + cl) + (i & 1) * 8;
+      }
     }
   }
   // contraction along D: row ln of the block, elements [16 ks + 8 g, +8)
-  S1F_DEV bf16x8 nat(const char *block, int ks) const { return *reinterpret_cast<const bf16x8 *>(block + nat_off[ks]); }
-  // contraction along the block's rows (slab t), operand index d = 32 db + ln; see TileOps::tr
-  S1F_DEV bf16x8 tr(const char *block, int t, int db) const {
-    const char *p = block + t * 16 * ROW_BYTES;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(S1F_LDS(s16x4, p + tr_off[db][0]));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(S1F_LDS(s16x4, p + tr_off[db][1]));
+  S1F_DEV bf16x8 nat(lds_addr block, int ks) const {
+    if (XOR_FORM) return lds_load<bf16x8>((block + nat_x) ^ (unsigned)(32 * ks));
+    return lds_load<bf16x8>(block + nat_off[ks]);
+  }
+  // contraction along the block's rows (slab t), operand index d = 32 db + ln.
+  // ds_read_b64_tr_b16: within each group of 16 lanes, lane i supplies the address of 4 consecutive
+  // 16-bit elements (row i/4 of a 4x16 matrix, columns 4*(i%4)..+3) and lane n receives column n of
+  // that matrix (4 rows).  Two reads give the 8 contraction slots of a slab: rows 16t+4g+{0..3} and
+  // 16t+8+4g+{0..3} of the block, for column d = 32*db + 16*(b&1) + n, b = lane/16.
+  S1F_DEV bf16x8 tr(lds_addr block, int t, int db) const {
+    lds_addr p0, p1;
+    if (XOR_FORM) {
+      p0 = ((block + tr_x) ^ (unsigned)(64 * db)) + t * 16 * ROW_BYTES;
+      p1 = ((block + tr_x) ^ (unsigned)((64 * db) ^ (32 + 2048))) + t * 16 * ROW_BYTES;
+    } else {
+      p0 = block + t * 16 * ROW_BYTES + tr_off[db][0];
+      p1 = block + t * 16 * ROW_BYTES + tr_off[db][1];
+    }
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        reinterpret_cast<__attribute__((address_space(3))) s16x4 *>((uintptr_t)p0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        reinterpret_cast<__attribute__((address_space(3))) s16x4 *>((uintptr_t)p1));
     typedef short s16x8 __attribute__((ext_vector_type(8)));
     s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, r);
@@ -213,8 +248,8 @@ template <int ROWS, int D> struct FragReader<LdsTile<float, ROWS, D>, float> {
   static constexpr int ROW_BYTES = TL::RS * 16;
   int lane_;
   S1F_DEV void init(int lane) { lane_ = lane; }
-  S1F_DEV float nat(const char *block, int ks) const { return TL::nat_frag(block, lane_ & 31, ks, lane_ >> 5); }
-  S1F_DEV float tr(const char *block, int t, int db) const { return TL::tr_frag(block, 0, t, db, lane_); }
+  S1F_DEV float nat(lds_addr block, int ks) const { return TL::nat_frag(lds_generic(block), lane_ & 31, ks, lane_ >> 5); }
+  S1F_DEV float tr(lds_addr block, int t, int db) const { return TL::tr_frag(lds_generic(block), 0, t, db, lane_); }
 };
 
 // Register-staged copy of a [ROWS x D] tile from global memory (row stride in elements) into an
@@ -256,24 +291,29 @@ template <typename T, int ROWS, int D, int NT> struct TileCopy {
   }
 };
 
-// Asynchronous copy of a [ROWS x D] tile from global memory straight into an LdsTile (no register
-// staging) by the NW waves of a workgroup.  One global_load_lds_dwordx4 moves 16 bytes per lane into 1 KiB
-// of consecutive LDS (lane l lands at base + 16*l), so the instruction that fills 16-byte slots
-// [64*n, 64*n+64) of the tile makes lane l fetch the chunk that the swizzle places in slot 64*n + l.
+// Asynchronous copy of a K tile and a V tile ([ROWS x D] each, V right behind K in LDS) from global
+// memory straight into LdsTiles (no register staging) by the NW waves of a workgroup.  One
+// global_load_lds_dwordx4 moves 16 bytes per lane into 1 KiB of consecutive LDS: lane l lands at
+// M0 + immediate offset + 16*l, and the immediate offset is added to the global address as well.  The
+// instruction that fills 16-byte slots [64*n, 64*n+64) of a tile makes lane l fetch the chunk that the
+// swizzle places in slot 64*n + l.  Each wave fills one contiguous range of the pair of tiles, and up to
+// four of its instructions share one value of M0 (told apart by the immediate offset): rewriting M0
+// between copies makes them complete one after the other instead of overlapping.
 // Rows past `rows_total` re-read the last valid row (callers mask them); slots of padding columns
 // (head_dim 80) re-read a valid chunk of the same row.  Completion is tracked by the wave's vmcnt.
-template <typename T, int ROWS, int D, int NW> struct AsyncTile {
+template <typename T, int ROWS, int D, int NW> struct AsyncTilePair {
   typedef LdsTile<T, ROWS, D> TL;
-  static constexpr int SLOTS = ROWS * TL::RS;
-  static constexpr int PER = SLOTS / (64 * NW);     // instructions per wave
-  static_assert(SLOTS % (64 * NW) == 0, "tile must split evenly over the workgroup's waves");
+  static constexpr int SLOTS = ROWS * TL::RS;           // 16-byte slots per tile
+  static constexpr int PER = 2 * SLOTS / (64 * NW);     // instructions per wave for the pair
+  static_assert((2 * SLOTS) % (64 * NW) == 0 && SLOTS % 64 == 0, "tiles must split evenly over the waves");
+  static_assert(PER <= 4 || PER % 4 == 0, "instructions are issued in groups of up to four");
   int row[PER];     // tile row fetched by this lane in instruction i
   int coff[PER];    // element offset of its chunk inside the row
 
   S1F_DEV void init(int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      const int slot = (wave * PER + i) * 64 + lane;
+      const int slot = ((wave * PER + i) * 64 + lane) % SLOTS;
       const int r = slot / TL::RS, pos = slot % TL::RS;
       int c = pos ^ TL::swz(r);
       if (TL::CPR < TL::RS && c >= TL::CPR) c &= TL::RS / 2 - 1;
@@ -281,17 +321,42 @@ template <typename T, int ROWS, int D, int NW> struct AsyncTile {
       coff[i] = c * TL::CE;
     }
   }
-  S1F_DEV void issue(const T *base, int64_t row_stride, int tile_row0, int rows_total, char *tile, int wave) const {
+
+  template <int N> S1F_DEV static void issue_group(unsigned dst, const T *p0, const T *p1, const T *p2, const T *p3) {
+    // Written as assembly so that the compiler's wait-count pass does not tie later LDS reads of OTHER
+    // ring stages to these copies (it would wait for them before the first LDS read); the callers order
+    // the copies against their readers with wait_async_tiles() + a workgroup barrier.
+    const char *q0 = reinterpret_cast<const char *>(p0), *q1 = reinterpret_cast<const char *>(p1) - 1024,
+               *q2 = reinterpret_cast<const char *>(p2) - 2048, *q3 = reinterpret_cast<const char *>(p3) - 3072;
+    if (N == 1)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(q0) : "m0");
+    else if (N == 2)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
+                   "global_load_lds_dwordx4 %2, off offset:1024" : : "s"(dst), "v"(q0), "v"(q1) : "m0");
+    else
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
+                   "global_load_lds_dwordx4 %2, off offset:1024\n\t"
+                   "global_load_lds_dwordx4 %3, off offset:2048\n\t"
+                   "global_load_lds_dwordx4 %4, off offset:3072" : : "s"(dst), "v"(q0), "v"(q1), "v"(q2), "v"(q3) : "m0");
+  }
+
+  // kbase/vbase: row 0 of the head's K and V; tile_row0: first row of the tile; stage: LDS address of the K tile
+  S1F_DEV void issue(const T *kbase, const T *vbase, int64_t row_stride, int tile_row0, int rows_total,
+                     lds_addr stage, int wave) const {
+    const T *p[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       int r = tile_row0 + row[i];
       r = r < rows_total ? r : rows_total - 1;
-      const T *p = base + (int64_t)r * row_stride + coff[i];
-      // Written as assembly so that the compiler's wait-count pass does not tie later LDS reads of OTHER
-      // ring stages to this copy (it would wait for it before the first LDS read); the callers order the
-      // copy against its readers with wait_async_tiles() + a workgroup barrier.
-      const unsigned dst = (unsigned)(uintptr_t)S1F_LDS(char, tile) + (unsigned)((wave * PER + i) * 1024);
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(p) : "m0");
+      const bool is_v = (wave * PER + i) * 64 >= SLOTS;     // wave-uniform
+      p[i] = (is_v ? vbase : kbase) + (int64_t)r * row_stride + coff[i];
+    }
+    static_assert(PER == 1 || PER == 2 || PER % 4 == 0, "group shape");
+    constexpr int G = PER < 4 ? PER : 4;
+#pragma unroll
+    for (int i = 0; i < PER; i += G) {
+      const unsigned dst = stage + (unsigned)((wave * PER + i) * 1024);
+      issue_group<G>(dst, p[i], p[G > 1 ? i + 1 : i], p[G > 2 ? i + 2 : i], p[G > 2 ? i + 3 : i]);
     }
   }
 };
@@ -309,6 +374,22 @@ template <> S1F_DEV void store4<bf16_t>(bf16_t *p, float a, float b, float c, fl
   *reinterpret_cast<bf16x4 *>(p) = r;
 }
 
+// Workgroup id -> (tile, batch*head).  The hardware hands consecutive workgroup ids to the 8 XCDs in turn,
+// and each XCD has its own L2.  All tiles of one (batch, head) stream the same K/V prefix (or the same
+// Q/dO segment), so they are given ids that land on one XCD, next to each other in time: the shared
+// operand is then fetched from HBM once per XCD instead of once per workgroup.  Falls back to the plain
+// order when the number of (batch, head) pairs is not a multiple of 8.
+S1F_DEV void decode_workgroup(int id, int n_tiles, int n_bh, int &tile, int &bh) {
+  if ((n_bh & 7) == 0) {
+    const int xcd = id & 7, slot = id >> 3;
+    bh = xcd + 8 * (slot / n_tiles);
+    tile = slot % n_tiles;
+  } else {
+    bh = id / n_tiles;
+    tile = id % n_tiles;
+  }
+}
+
 // Arguments common to the three kernels (all strides in elements of the tensor they index).
 struct AttnArgs {
   const void *q, *k, *v, *out, *dout;   // out: written by fwd, read by bwd
@@ -320,7 +401,12 @@ struct AttnArgs {
   int64_t kv_sb, kv_sh, kv_ss;
   int32_t seg_off, seg_len;
   int32_t n_q_heads, group;              // group = Hq / Hkv
+  int32_t n_tiles, n_bh;                 // launch shape: tiles per (batch, head) and number of (batch, head) pairs
   float scale;                           // 1/sqrt(head_dim)
+#ifdef S1F_TRACE
+  unsigned long long *trace;             // development aid: cycle stamps of one wave
+  unsigned trace_wg, trace_tid;
+#endif
 };
 
 }  // namespace s1f

@@ -17,6 +17,13 @@
 #pragma once
 #include "attn_device.hpp"
 
+// Optional cycle tracing of one wave (development aid, compiled out unless S1F_TRACE is defined).
+#ifdef S1F_TRACE
+#define S1F_TRACE_MARK(slot) do { if (trace_on) trace_t[slot] = __builtin_readcyclecounter(); } while (0)
+#else
+#define S1F_TRACE_MARK(slot) do { } while (0)
+#endif
+
 namespace s1f {
 
 // Lazy rescaling: the running maximum m of a row is only raised when the new block's maximum exceeds it by
@@ -35,12 +42,12 @@ template <typename T, int D, int NQ, int KB, int NW> struct FwdCfg {
 };
 
 // Number of operand fragments a wave keeps in flight ahead of the matrix instruction that consumes them
-// (LDS latency is about three 32x32x16 MFMAs).
+// (LDS latency is three to four 32x32x16 MFMAs).
 constexpr int kPrefetch = 3;
 
 // S^T blocks of one 32-key block: s[nq] = K[block rows, :] Q^T   (prologue only; the loop uses fwd_step)
 template <typename RD, typename T, int NQ, int NKS>
-S1F_DEV void fwd_scores(f32x16 (&s)[NQ], const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd, const char *kblock) {
+S1F_DEV void fwd_scores(f32x16 (&s)[NQ], const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd, lds_addr kblock) {
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
@@ -77,17 +84,26 @@ template <int NQ> S1F_DEV void fwd_row_max(const f32x16 (&s)[NQ], float (&mx)[NQ
 
 // One pipelined step over block k, whose scores are in `s` with m already covering them:
 //   phase 1   sn = scores of block k+1 (matrix pipe)  ||  p = exp2(s*c - m), row sums (vector pipe)
-//   phase 2   O += P V of block k (matrix pipe)
-// Operand fragments are read from LDS kPrefetch matrix instructions ahead of their use; the scheduling
-// fences keep that order in the generated code.
-template <typename RD, typename T, bool HAS_NEXT, int NQ, int NKS, int DB>
+//   phase 2   O += P V of block k (matrix pipe)        ||  mask and row maximum of sn (vector pipe)
+// Operand fragments are read from LDS kPrefetch matrix instructions ahead of their use (the V fragments
+// of phase 2 start arriving during the last slots of phase 1); the scheduling fences keep that order in
+// the generated code.  On return mx holds the row maxima of block k+1 in log2 units.
+//   lim0_next = (absolute row of this lane's query in query block 0) - (first key of block k+1) - 4g
+template <typename RD, typename T, bool HAS_NEXT, bool MASK_NEXT, int NQ, int NKS, int DB>
 S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], const float (&m)[NQ], float (&l)[NQ],
-                      const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd, const char *kblock_next,
-                      const char *vblock, float c) {
+                      float (&mx)[NQ], const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd,
+                      lds_addr kblock_next, lds_addr vblock, float c, int lim0_next
+#ifdef S1F_TRACE
+                      , bool trace_on, unsigned long long (&trace_t)[8]
+#endif
+                      ) {
   typedef typename Elem<T>::Frag Frag;
   constexpr int NSLAB = 16 / Elem<T>::EPL;
   constexpr int PF = kPrefetch;
+  constexpr int NV = NSLAB * DB;   // V fragments of the block, in the order (slab, d-block)
+  static_assert(NKS >= PF && NV >= PF, "prefetch ring deeper than the products");
 
+  Frag vf[PF];
   float rs[NQ];
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) rs[nq] = 0.f;
@@ -98,12 +114,17 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
       for (int v = 0; v < 16; ++v) sn[nq][v] = 0.f;
     Frag kf[PF];
 #pragma unroll
-    for (int i = 0; i < PF && i < NKS; ++i) kf[i] = rd.nat(kblock_next, i);
+    for (int i = 0; i < PF; ++i) kf[i] = rd.nat(kblock_next, i);
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) sn[nq] = mma(kf[ks % PF], qf[nq][ks], sn[nq]);
-      if (ks + PF < NKS) kf[ks % PF] = rd.nat(kblock_next, ks + PF);
+      if (ks + PF < NKS) {
+        kf[ks % PF] = rd.nat(kblock_next, ks + PF);
+      } else {   // the K ring drains: its slots go to the first V fragments
+        const int i = ks + PF - NKS;
+        vf[i] = rd.tr(vblock, i / DB, i % DB);
+      }
       // this slot's share of the 16 exponentials per query block
 #pragma unroll
       for (int v = 16 * ks / NKS; v < 16 * (ks + 1) / NKS; ++v)
@@ -117,6 +138,8 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
     }
   } else {
 #pragma unroll
+    for (int i = 0; i < PF; ++i) vf[i] = rd.tr(vblock, i / DB, i % DB);
+#pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -127,11 +150,11 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
   }
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) l[nq] += rs[nq];
+  S1F_TRACE_MARK(2);
 
-  constexpr int NV = NSLAB * DB;   // V fragments of the block, in the order (slab, d-block)
-  Frag vf[PF];
+  float mxv[NQ];
 #pragma unroll
-  for (int i = 0; i < PF && i < NV; ++i) vf[i] = rd.tr(vblock, i / DB, i % DB);
+  for (int nq = 0; nq < NQ; ++nq) mxv[nq] = -INFINITY;
 #pragma unroll
   for (int t = 0; t < NSLAB; ++t) {
     Frag pf[NQ];
@@ -143,8 +166,22 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) o[nq][db] = mma(vf[i % PF], pf[nq], o[nq][db]);
       if (i + PF < NV) vf[i % PF] = rd.tr(vblock, (i + PF) / DB, (i + PF) % DB);
+      if (HAS_NEXT) {   // this slot's share of masking and maximum over the next block's 16 scores per query block
+#pragma unroll
+        for (int v = 16 * i / NV; v < 16 * (i + 1) / NV; ++v)
+#pragma unroll
+          for (int nq = 0; nq < NQ; ++nq) {
+            if (MASK_NEXT && 8 * (v >> 2) + (v & 3) > lim0_next + 32 * nq) sn[nq][v] = -INFINITY;
+            mxv[nq] = fmaxf(mxv[nq], sn[nq][v]);
+          }
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
+  }
+  S1F_TRACE_MARK(3);
+  if (HAS_NEXT) {
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) mx[nq] = max_xor32(mxv[nq]) * c;
   }
 }
 
@@ -158,11 +195,13 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   constexpr int DB = KT::DPAD / 32, BM = Cfg::BM, BN = Cfg::BN;
   static_assert(D % KSTEP == 0, "shape");
 
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  extern __shared__ __attribute__((aligned(8192))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;   // later (heavier) row tiles are scheduled first
-  const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
+  int qt, bh;
+  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, qt, bh);
+  qt = a.n_tiles - 1 - qt;   // later (heavier) row tiles are scheduled first
+  const int h = bh % a.n_q_heads, b = bh / a.n_q_heads, hk = h / a.group;
   const int seg_off = a.seg_off, seg_len = a.seg_len, kv_len = seg_off + seg_len;
   const int row0 = qt * BM, wrow0 = row0 + wave * 32 * NQ;
 
@@ -174,12 +213,11 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   const int n_blk = (seg_off + last_row) / 32 + 1;           // 32-key blocks holding keys 0 .. seg_off+last_row
   const int n_kt = (n_blk + KB - 1) / KB;
 
-  AsyncTile<T, BN, D, NW> ld;
+  const lds_addr lds0 = to_lds_addr(smem);
+  AsyncTilePair<T, BN, D, NW> ld;
   ld.init(wave, lane);
   auto issue = [&](int jt) {
-    char *st = smem + (jt % 3) * Cfg::STAGE_BYTES;
-    ld.issue(kbase, a.kv_ss, jt * BN, kv_len, st, wave);
-    ld.issue(vbase, a.kv_ss, jt * BN, kv_len, st + KT::BYTES, wave);
+    ld.issue(kbase, vbase, a.kv_ss, jt * BN, kv_len, lds0 + (jt % 3) * Cfg::STAGE_BYTES, wave);
   };
   issue(0);
   if (n_kt > 1) issue(1);
@@ -215,7 +253,7 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   __syncthreads();
   f32x16 s[NQ], sn[NQ];
   float mx[NQ];
-  fwd_scores<FragReader<KT, T>, T, NQ, NKS>(s, qf, rd, smem);
+  fwd_scores<FragReader<KT, T>, T, NQ, NKS>(s, qf, rd, lds0);
   if (31 > seg_off + wrow0) fwd_mask(s, seg_off + wrow0 + ln - 4 * g);
   fwd_row_max(s, mx, c);
 #pragma unroll
@@ -223,30 +261,53 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
 
   // The steady loop never touches O except through the matrix pipe.  When some row of the wave has to
   // raise its running maximum the loop is left, O and l are rescaled, and the loop is entered again.
+  typedef FragReader<KT, T> RD;
+#ifdef S1F_TRACE
+  unsigned long long trace_t[8] = {};
+  const bool trace_on = a.trace != nullptr && blockIdx.x == a.trace_wg && tid == a.trace_tid;
+#define S1F_TRACE_ARGS , trace_on, trace_t
+#else
+#define S1F_TRACE_ARGS
+#endif
   int k = 0;
   while (true) {
     bool raise_any = false;
     while (k + 1 < n_blk) {
       const int jt = k / KB, kb = k % KB;
+      S1F_TRACE_MARK(0);
       if (kb == KB - 1) {
         wait_async_tiles();   // this wave's part of tile jt+1 has landed (it was issued a whole tile ago)
+#ifdef S1F_TRACE
+        S1F_TRACE_MARK(5);
+#endif
         __syncthreads();      // ... and everyone's; every wave has also finished reading tile jt-1
+        S1F_TRACE_MARK(6);
         if (jt + 2 < n_kt) issue(jt + 2);
       }
-      const char *vblock = smem + (jt % 3) * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
+      S1F_TRACE_MARK(1);
+      const lds_addr vblock = lds0 + (jt % 3) * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
       const int kn = k + 1;
-      const char *kblock_next = smem + ((kn / KB) % 3) * Cfg::STAGE_BYTES + (kn % KB) * BLOCK_BYTES;
-      fwd_step<FragReader<KT, T>, T, true>(s, sn, o, m, l, qf, rd, kblock_next, vblock, c);
+      const lds_addr kblock_next = lds0 + ((kn / KB) % 3) * Cfg::STAGE_BYTES + (kn % KB) * BLOCK_BYTES;
+      const int lim0n = seg_off + wrow0 + ln - 32 * kn - 4 * g;
       // the last block always crosses the diagonal; earlier ones do if their last key is past the wave's first row
-      if (kn + 1 == n_blk || 32 * kn + 31 > seg_off + wrow0) fwd_mask(sn, seg_off + wrow0 + ln - 32 * kn - 4 * g);
-      fwd_row_max(sn, mx, c);
+      if (kn + 1 == n_blk || 32 * kn + 31 > seg_off + wrow0)
+        fwd_step<RD, T, true, true>(s, sn, o, m, l, mx, qf, rd, kblock_next, vblock, c, lim0n S1F_TRACE_ARGS);
+      else
+        fwd_step<RD, T, true, false>(s, sn, o, m, l, mx, qf, rd, kblock_next, vblock, c, lim0n S1F_TRACE_ARGS);
+      S1F_TRACE_MARK(4);
+#ifdef S1F_TRACE
+      if (trace_on && k >= 300 && k < 364) {
+        unsigned long long *dst = a.trace + (size_t)(k - 300) * 8;
+        for (int i = 0; i < 7; ++i) dst[i] = trace_t[i];
+      }
+#endif
+      k = kn;
       bool raise = false;
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
         s[nq] = sn[nq];
         raise = raise || (mx[nq] > m[nq] + kRescaleTau);
       }
-      k = kn;
       if (__builtin_amdgcn_ballot_w64(raise) != 0) { raise_any = true; break; }
     }
     if (!raise_any) break;
@@ -262,8 +323,8 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   }
   {   // last block: no next scores to compute
     const int jt = k / KB, kb = k % KB;
-    const char *vblock = smem + (jt % 3) * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
-    fwd_step<FragReader<KT, T>, T, false>(s, sn, o, m, l, qf, rd, vblock, vblock, c);
+    const lds_addr vblock = lds0 + (jt % 3) * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
+    fwd_step<RD, T, false, false>(s, sn, o, m, l, mx, qf, rd, vblock, vblock, c, 0 S1F_TRACE_ARGS);
   }
 
   T *ob = reinterpret_cast<T *>(a.out_w) + b * a.q_sb + h * a.q_sh;

@@ -14,8 +14,14 @@ using namespace s1f;
 // Tile shapes per element type: query blocks per wave (NQ), key blocks per wave (NK), keys per staged
 // K/V tile (BN), rows per staged Q/dO tile (BQ).
 template <typename T> struct Shape;
-template <> struct Shape<bf16_t> { static constexpr int NQ = 1, KB = 2, NW = 8, BN = 64, OCC = 2, NK = 1, BQ = 64; };
-template <> struct Shape<float>  { static constexpr int NQ = 1, KB = 1, NW = 4, BN = 32, OCC = 1, NK = 1, BQ = 32; };
+//   forward: FNQ query blocks per wave, FKB 32-key blocks per LDS tile, FNW waves, FOCC waves per SIMD
+//   dq:      QNQ, QBN keys per LDS tile, QOCC;   dk/dv: NK key blocks per wave, BQ rows per Q/dO tile
+template <> struct Shape<bf16_t> {
+  static constexpr int FNQ = 1, FKB = 2, FNW = 8, FOCC = 2, QNQ = 1, QBN = 32, QOCC = 2, NK = 1, BQ = 64;
+};
+template <> struct Shape<float> {
+  static constexpr int FNQ = 1, FKB = 1, FNW = 4, FOCC = 1, QNQ = 1, QBN = 32, QOCC = 1, NK = 1, BQ = 32;
+};
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -51,7 +57,12 @@ AttnArgs make_args(const s1f_desc *d, int64_t seg_off, int64_t seg_len) {
   return a;
 }
 
-template <typename K> int launch(K kernel, dim3 grid, int threads, int lds_bytes, const AttnArgs &a, hipStream_t st) {
+// One-dimensional grid of n_tiles * n_bh workgroups; the kernels decode (tile, batch*head) themselves.
+template <typename K> int launch(K kernel, int n_tiles, int n_bh, int threads, int lds_bytes, AttnArgs a, hipStream_t st) {
+  if ((int64_t)n_tiles * n_bh > 0x7fffffff) return S1F_EUNSUPPORTED;
+  a.n_tiles = n_tiles;
+  a.n_bh = n_bh;
+  const dim3 grid((unsigned)((int64_t)n_tiles * n_bh));
   if (lds_bytes > 64 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                             lds_bytes) != hipSuccess)
@@ -63,24 +74,24 @@ template <typename K> int launch(K kernel, dim3 grid, int threads, int lds_bytes
 
 template <typename T, int D> int fwd_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
   typedef Shape<T> S;
-  typedef FwdCfg<T, D, S::NQ, S::KB, S::NW> Cfg;
-  const dim3 grid((a.seg_len + Cfg::BM - 1) / Cfg::BM, d->n_q_heads, d->batch);
-  return launch(seg_attn_fwd_kernel<T, D, S::NQ, S::KB, S::NW, S::OCC>, grid, Cfg::THREADS, Cfg::LDS_BYTES, a, st);
+  typedef FwdCfg<T, D, S::FNQ, S::FKB, S::FNW> Cfg;
+  return launch(seg_attn_fwd_kernel<T, D, S::FNQ, S::FKB, S::FNW, S::FOCC>, (a.seg_len + Cfg::BM - 1) / Cfg::BM,
+                d->n_q_heads * d->batch, Cfg::THREADS, Cfg::LDS_BYTES, a, st);
 }
 
 template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
   typedef Shape<T> S;
-  typedef BwdDqCfg<T, D, S::NQ, S::BN> QC;
-  const dim3 gq((a.seg_len + QC::BM - 1) / QC::BM, d->n_q_heads, d->batch);
-  return launch(seg_attn_bwd_dq_kernel<T, D, S::NQ, S::BN, S::OCC>, gq, 256, QC::LDS_BYTES, a, st);
+  typedef BwdDqCfg<T, D, S::QNQ, S::QBN> QC;
+  return launch(seg_attn_bwd_dq_kernel<T, D, S::QNQ, S::QBN, S::QOCC>, (a.seg_len + QC::BM - 1) / QC::BM,
+                d->n_q_heads * d->batch, 256, QC::LDS_BYTES, a, st);
 }
 
 template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
   typedef Shape<T> S;
   typedef BwdDkdvCfg<T, D, S::NK, S::BQ> KC;
   const int kv_len = a.seg_off + a.seg_len;
-  const dim3 gk((kv_len + KC::BNW - 1) / KC::BNW, d->n_kv_heads, d->batch);
-  return launch(seg_attn_bwd_dkdv_kernel<T, D, S::NK, S::BQ>, gk, 256, KC::LDS_BYTES, a, st);
+  return launch(seg_attn_bwd_dkdv_kernel<T, D, S::NK, S::BQ>, (kv_len + KC::BNW - 1) / KC::BNW,
+                d->n_kv_heads * d->batch, 256, KC::LDS_BYTES, a, st);
 }
 
 
