@@ -59,7 +59,7 @@ class Stage:
         self.dk = torch.empty((1, w.n_kv_heads, n, d), device="cuda", dtype=torch.float32)
         self.dv = torch.empty_like(self.dk)
         self.lse_flat = torch.empty(w.n_q_heads * n, device="cuda", dtype=torch.float32)
-        self.ws = torch.empty(w.n_q_heads * n, device="cuda", dtype=torch.float32)
+        self.ws = torch.empty(2 * w.n_q_heads * (n + 64), device="cuda", dtype=torch.float32)
         self.events = []     # (kind, segment, start, end) recorded inside timed steps
 
     def boundaries(self, n_seg=None, kind=None):
