@@ -31,7 +31,21 @@ def parse():
     ap.add_argument("--workload", default="7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unsegmented", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one 1 GiB device-to-device copy first (reference for HBM byte counters)")
     return ap.parse_args()
+
+
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for this workload
+    (recorded in the summaries under profiles/), or None if no profile covers it."""
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel and f[2] == workload:
+                return float(f[3])
+    return None
 
 
 def seg_pairs(bounds):
@@ -114,24 +128,29 @@ class Stage:
 
 def cpu_baseline(stage, torch):
     """The row oracle, as it stands, timed on this machine's host cores on a bounded sample of the workload:
-    one head, the first `ns` tokens, full causal forward + backward."""
+    the first `ns` tokens of a few heads, full causal forward + backward (about 5e8 (query, key) pairs)."""
     from oracle import rows
     w = stage.w
-    ns = min(w.seq_len, 8192 if w.head_dim >= 128 else 8192)
-    g = 0
-    q = stage.q[0, 0:1, :ns].float().cpu().numpy()
-    do = stage.dout[0, 0:1, :ns].float().cpu().numpy()
-    k = stage.k[0, g:g + 1, :ns].float().cpu().numpy()
-    v = stage.v[0, g:g + 1, :ns].float().cpu().numpy()
+    ns = min(w.seq_len, 32768)
+    pairs = ns * (ns + 1) // 2
+    heads = max(1, min(w.n_q_heads, round(5.4e8 / pairs)))
+    grp = w.n_q_heads // w.n_kv_heads
     rows.build()
-    t0 = time.perf_counter()
-    rows.forward_rows(q, k, v, 0, 0, ns)
-    rows.dq_rows(q, k, v, do, 0, 0, ns)
-    rows.dkdv_keys(q, k, v, do, 0, 0, ns)
-    dt = time.perf_counter() - t0
-    flops = 14.0 * w.head_dim * (ns * (ns + 1) // 2)
+    dt = 0.0
+    for h in range(heads):
+        g = h // grp
+        q = stage.q[0, h:h + 1, :ns].float().cpu().numpy()
+        do = stage.dout[0, h:h + 1, :ns].float().cpu().numpy()
+        k = stage.k[0, g:g + 1, :ns].float().cpu().numpy()
+        v = stage.v[0, g:g + 1, :ns].float().cpu().numpy()
+        t0 = time.perf_counter()
+        rows.forward_rows(q, k, v, 0, 0, ns)
+        rows.dq_rows(q, k, v, do, 0, 0, ns)
+        rows.dkdv_keys(q, k, v, do, 0, 0, ns)
+        dt += time.perf_counter() - t0
+    flops = 14.0 * w.head_dim * pairs * heads
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": rows.threads(), "kind": "oracle",
-            "sample": f"fp64 row oracle, one head, first {ns} tokens of the {w.name} workload, full causal "
+            "sample": f"fp64 row oracle, {heads} head(s), first {ns} tokens of the {w.name} workload, full causal "
                       f"forward+backward ({dt:.1f} s)", "seconds": dt}
 
 
@@ -149,6 +168,12 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     w = S.WORKLOADS[args.workload]
+    if args.calibrate_copy:   # a plain copy of known size: 1 GiB read + 1 GiB written
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     stage = Stage(w, torch, s1f)
     ms = stage.run(args.steps, args.warmup)
     bounds = stage.boundaries()
@@ -175,8 +200,10 @@ def main():
     roofline = {"bound": "mfma", "kernel": {"fwd": "seg_attn_fwd_kernel", "bwd_dq": "seg_attn_bwd_dq_kernel",
                                             "bwd_dkdv": "seg_attn_bwd_dkdv_kernel"}[dom],
                 "achieved": kernels[dom]["alg_tflops"], "peak": peak, "unit": "TFLOP/s",
-                "frac": kernels[dom]["alg_tflops"] / peak, "traffic": None,
+                "frac": kernels[dom]["alg_tflops"] / peak, "traffic": None, "traffic_unit": "bytes per launch",
                 "avg_launch_ms": kernels[dom]["avg_launch_ms"]}
+
+    roofline["traffic"] = measured_traffic(roofline["kernel"], w.name)
 
     result = {
         "metric": "segmented causal attn fwd+bwd TFLOP/s on 1 GPU; % of bf16 MFMA peak",
