@@ -38,7 +38,7 @@ extern "C" {
 typedef enum {
   S1F_OK = 0,
   S1F_EINVAL = 1,       /* null pointer, non-positive size, inconsistent descriptor */
-  S1F_EUNSUPPORTED = 2, /* dtype / head_dim combination without a kernel */
+  S1F_EUNSUPPORTED = 2, /* dtype / head_dim combination without a kernel, or a size beyond a kernel's limits */
   S1F_ERANGE = 3,       /* segment does not fit: seg_off < 0, seg_len < 1, seg_off + seg_len > kv_capacity */
   S1F_EDEVICE = 4       /* the HIP runtime reported an error at launch */
 } s1f_status;
@@ -96,8 +96,11 @@ int s1f_seg_attn_fwd(const s1f_desc *desc, const void *q_seg, const void *k_pref
  *             LAST segment and calls segments in reverse order; after the call for segment i, rows
  *             [seg_off, seg_off+seg_len) hold final gradients.
  *   workspace device scratch of at least s1f_bwd_workspace_bytes(desc, seg_off, seg_len) bytes
- *             (holds delta = rowsum(dout * out) in fp32); contents are undefined afterwards.
- * Errors as above, plus S1F_EINVAL if workspace is NULL or workspace_bytes is too small. */
+ *             (two fp32 values per query row and head: -lse/scale and -rowsum(dout * out), the row
+ *             statistics the dK/dV kernel starts its products from); contents are undefined afterwards.
+ * Errors as above, plus S1F_EINVAL if workspace is NULL or workspace_bytes is too small, and
+ * S1F_EUNSUPPORTED if q_stride_s >= 2^23 elements or batch * n_q_heads * seg_len > 2^28 (the kernels'
+ * asynchronous copies use 32-bit byte offsets inside a tile and inside the workspace). */
 int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
                      const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
                      int64_t seg_len, void *dq, float *dk_prefix_acc, float *dv_prefix_acc,
@@ -105,9 +108,10 @@ int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const void *q_seg, 
 
 /* The two halves of s1f_seg_attn_bwd as separate calls (same arguments, same validation), for callers
  * that schedule or time them separately; s1f_seg_attn_bwd is exactly _dq followed by _dkdv on one stream.
- *   s1f_seg_attn_bwd_dq    overwrites dq and writes delta = rowsum(dout * out) into workspace
- *   s1f_seg_attn_bwd_dkdv  reads lse and the delta left in workspace by _dq for the same segment, and
- *                          updates dk_prefix_acc / dv_prefix_acc */
+ *   s1f_seg_attn_bwd_dq    overwrites dq and writes the row statistics (-lse/scale, -rowsum(dout * out))
+ *                          into workspace
+ *   s1f_seg_attn_bwd_dkdv  reads the statistics left in workspace by _dq for the same segment (lse is
+ *                          validated but not read) and updates dk_prefix_acc / dv_prefix_acc */
 int s1f_seg_attn_bwd_dq(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
                         const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
                         int64_t seg_len, void *dq, void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -67,7 +67,10 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
     }
     delta[nq] = sum_xor32(part);
     lse2[nq] = a.lse[lse_off + rc] * kLog2e;
-    if (r < seg_len && g == 0) a.delta[lse_off + r] = delta[nq];
+    if (r < seg_len && g == 0) {   // row statistics for the dK/dV kernel
+      a.delta[lse_off + r] = -a.lse[lse_off + r] / a.scale;
+      a.delta[a.ws_plane + lse_off + r] = -delta[nq];
+    }
   }
 
   f32x16 dq[NQ][DB];
@@ -173,28 +176,38 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
 template <typename T, int D, int NK, int BQ> struct BwdDkdvCfg {
   static constexpr int BNW = 128 * NK;                 // keys per workgroup
   typedef LdsTile<T, BQ, D> QT;
-  static constexpr int STAT_BYTES = 2 * BQ * 4;        // lse*log2(e) and delta of the tile's rows
-  static constexpr int BUF_BYTES = 2 * QT::BYTES + STAT_BYTES;
-  static constexpr int LDS_BYTES = 2 * BUF_BYTES;      // double buffered
+  static constexpr int STAGE_BYTES = 2 * QT::BYTES;    // Q tile, dO tile right behind it
+  static constexpr int STAT_BYTES = 2 * BQ * 4;        // -lse/scale and -delta of the tile's rows
+  typedef LdsTile<T, BNW, D> VT;                       // the workgroup's V rows
+  static constexpr int LDS_BYTES = 2 * STAGE_BYTES + VT::BYTES + 2 * STAT_BYTES;   // two stages, V, statistics
+  static_assert(STAGE_BYTES % 8192 == 0, "stages must keep the 8 KiB alignment of the fragment reader");
 };
 
 // Lane = one key (column ln); queries run over registers.
 //   S[q][key]  = Q K^T         A = Q (LDS),              B = K (registers)
-//   dP[q][key] = dO V^T        A = dO (LDS),             B = V (registers)
+//   dP[q][key] = dO V^T        A = dO (LDS),             B = V (LDS)
 //   dV^T[d][key] += dO^T P     A = dO read transposed,   B = P slab (registers)
 //   dK^T[d][key] += Q^T dS     A = Q read transposed,    B = dS slab (registers)
-template <typename T, int D, int NK, int BQ>
-__global__ void __launch_bounds__(256) seg_attn_bwd_dkdv_kernel(const AttnArgs a) {
+// The wave's K fragments, its dK and dV accumulators and the block's S and dP fill the register budget of
+// two waves per SIMD; its V rows are therefore read from LDS (copied there once).
+// Q/dO tiles and their row statistics are copied HBM -> LDS asynchronously (no staging registers) one tile
+// ahead of their use, so that two workgroups fit on a compute unit and fill each other's barrier and
+// latency gaps.
+template <typename T, int D, int NK, int BQ, int OCC = 1>
+__global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnArgs a) {
   typedef Elem<T> E;
   typedef typename E::Frag Frag;
   typedef BwdDkdvCfg<T, D, NK, BQ> Cfg;
   typedef LdsTile<T, BQ, D> QT;
+  typedef FragReader<QT, T> RD;
   constexpr int EPL = E::EPL, KSTEP = 2 * EPL, NKS = D / KSTEP;
   constexpr int DB = QT::DPAD / 32, NSLAB = 16 / EPL, QB = BQ / 32;
+  constexpr int BLOCK_BYTES = 32 * QT::RS * 16;
   static_assert(BQ % 32 == 0 && 2 * BQ <= 256, "query tile");
 
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  extern __shared__ __attribute__((aligned(8192))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int kt, bh;
   decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, kt, bh);   // early key tiles see every query row: heaviest first
   const int n_kv_heads = a.n_q_heads / a.group;
@@ -207,26 +220,6 @@ __global__ void __launch_bounds__(256) seg_attn_bwd_dkdv_kernel(const AttnArgs a
   const T *kbase = reinterpret_cast<const T *>(a.k) + kvoff;
   const T *vbase = reinterpret_cast<const T *>(a.v) + kvoff;
 
-  Frag kf[NK][NKS], vf[NK][NKS];
-#pragma unroll
-  for (int nk = 0; nk < NK; ++nk) {
-    int key = wkey0 + 32 * nk + ln;
-    key = key < kv_len ? key : kv_len - 1;     // keys past the prefix are computed on a copy and never stored
-    const int64_t off = (int64_t)key * a.kv_ss + EPL * g;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      kf[nk][ks] = load_frag_global<T>(kbase + off + ks * KSTEP);
-      vf[nk][ks] = load_frag_global<T>(vbase + off + ks * KSTEP);
-    }
-  }
-  f32x16 dk[NK][DB], dv[NK][DB];
-#pragma unroll
-  for (int nk = 0; nk < NK; ++nk)
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) { dk[nk][db][v] = 0.f; dv[nk][db][v] = 0.f; }
-
   // First query row that can see any key of this workgroup, and the tile holding it.
   const int r_first = j0 > seg_off ? j0 - seg_off : 0;
   const int qt_first = r_first / BQ;
@@ -236,38 +229,66 @@ __global__ void __launch_bounds__(256) seg_attn_bwd_dkdv_kernel(const AttnArgs a
   const float c = a.scale * kLog2e;
   const bool w_active = wkey0 < kv_len;
 
-  TileCopy<T, BQ, D, 256> cq, cdo;
-  float stat = 0.f;   // one lse2 or delta value staged by threads 0 .. 2*BQ-1
+  const lds_addr lds0 = to_lds_addr(smem);
+  const lds_addr vtile = lds0 + 2 * Cfg::STAGE_BYTES;
+  const lds_addr stats0 = vtile + Cfg::VT::BYTES;
+  const float *stats_lds = reinterpret_cast<const float *>(smem + 2 * Cfg::STAGE_BYTES + Cfg::VT::BYTES);
+  AsyncTilePairU<T, BQ, D, 4> ld;
+  ld.init(wave, lane, a.q_ss);
+  RD rd;
+  rd.init(lane);
+  // statistics: lane `lane` of wave w < 2*BQ/64 copies entry 64*w + lane of {-lse/scale [BQ], -delta [BQ]}
+  const int st_idx = wave * 64 + lane, st_row = st_idx % BQ;
+  const unsigned st_plane = (unsigned)((st_idx / BQ) * a.ws_plane);
 
-  auto issue = [&](int it) {
+  auto issue = [&](int it) {   // tile `it` (head-major) -> stage it & 1; rows past the segment re-read its last row
     const int hq = hk * a.group + it / per_head;
     const int r0 = (qt_first + it % per_head) * BQ;
-    const int64_t qoff = b * a.q_sb + hq * a.q_sh + (int64_t)r0 * a.q_ss;
-    cq.load(reinterpret_cast<const T *>(a.q) + qoff, a.q_ss, seg_len - r0, tid);
-    cdo.load(reinterpret_cast<const T *>(a.dout) + qoff, a.q_ss, seg_len - r0, tid);
-    if (tid < 2 * BQ) {
-      const int rr = r0 + (tid % BQ);
-      const int64_t so = ((int64_t)b * a.n_q_heads + hq) * seg_len + (rr < seg_len ? rr : seg_len - 1);
-      stat = tid < BQ ? a.lse[so] * kLog2e : a.delta[so];
+    const int64_t qoff = b * a.q_sb + hq * a.q_sh;
+    ld.issue(reinterpret_cast<const T *>(a.q) + qoff, reinterpret_cast<const T *>(a.dout) + qoff, a.q_ss, r0, seg_len,
+             lds0 + (it & 1) * Cfg::STAGE_BYTES, wave, lane);
+    if (wave < 2 * BQ / 64) {
+      const int rr = r0 + st_row;
+      const float *sb = a.delta + ((int64_t)b * a.n_q_heads + hq) * seg_len;     // wave-uniform
+      const unsigned so = (st_plane + (unsigned)(rr < seg_len ? rr : seg_len - 1)) * 4u;
+      const unsigned dst = stats0 + (unsigned)((it & 1) * Cfg::STAT_BYTES + wave * 256);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(so), "s"(sb) : "m0");
     }
   };
-  auto commit = [&](int buf) {
-    char *base = smem + buf * Cfg::BUF_BYTES;
-    cq.store(base, tid);
-    cdo.store(base + QT::BYTES, tid);
-    if (tid < 2 * BQ) reinterpret_cast<float *>(base + 2 * QT::BYTES)[tid] = stat;
-  };
 
+  // V rows of the workgroup's keys -> LDS (rows past the prefix are zero: their products are never stored)
+  {
+    TileCopy<T, Cfg::BNW, D, 256> cv;
+    cv.load(vbase + (int64_t)j0 * a.kv_ss, a.kv_ss, kv_len - j0, tid);
+    cv.store(smem + 2 * Cfg::STAGE_BYTES, tid);
+  }
+  // K fragments of the wave's keys stay in registers for the whole kernel.
+  Frag kf[NK][NKS];
+#pragma unroll
+  for (int nk = 0; nk < NK; ++nk) {
+    int key = wkey0 + 32 * nk + ln;
+    key = key < kv_len ? key : kv_len - 1;     // keys past the prefix are computed on a copy and never stored
+    const int64_t off = (int64_t)key * a.kv_ss + EPL * g;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) kf[nk][ks] = load_frag_global<T>(kbase + off + ks * KSTEP);
+  }
   issue(0);
-  commit(0);
+  f32x16 dk[NK][DB], dv[NK][DB];
+#pragma unroll
+  for (int nk = 0; nk < NK; ++nk)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { dk[nk][db][v] = 0.f; dv[nk][db][v] = 0.f; }
+  wait_async_tiles();
   __syncthreads();
 
   for (int it = 0; it < n_it; ++it) {
-    const char *base = smem + (it & 1) * Cfg::BUF_BYTES;
-    const char *qtile = base, *dotile = base + QT::BYTES;
-    const float *lse2s = reinterpret_cast<const float *>(base + 2 * QT::BYTES);
-    const float *deltas = lse2s + BQ;
+    const lds_addr qtile = lds0 + (it & 1) * Cfg::STAGE_BYTES;
+    const float *nlses = stats_lds + (it & 1) * 2 * BQ;   // -lse/scale of the tile's rows, then -delta
+    const float *ndeltas = nlses + BQ;
     const int r0 = (qt_first + it % per_head) * BQ;
+    // the other stage was last read before the barrier that ended the previous iteration
     if (it + 1 < n_it) issue(it + 1);
 
     if (w_active && wkey0 <= seg_off + r0 + BQ - 1) {
@@ -275,43 +296,56 @@ __global__ void __launch_bounds__(256) seg_attn_bwd_dkdv_kernel(const AttnArgs a
       for (int qb = 0; qb < QB; ++qb) {
         const int rb = r0 + 32 * qb;   // first row of this 32-row block
         if (wkey0 > seg_off + rb + 31 || rb >= seg_len) continue;
+        const lds_addr qblock = qtile + qb * BLOCK_BYTES;   // the dO block lies QT::BYTES behind it
+        // The accumulators start from the row statistics instead of zero (register v holds row
+        // rb + 8*(v/4) + 4*g + v%4): s = q.k - lse/scale and dp = dO.v - delta come out of the matrix
+        // pipe ready for p = exp2(c*s) and dS = p*dp.
         f32x16 s[NK], dp[NK];
 #pragma unroll
-        for (int nk = 0; nk < NK; ++nk)
+        for (int vq = 0; vq < 4; ++vq) {
+          const f32x4 nl = *reinterpret_cast<const f32x4 *>(nlses + 32 * qb + 8 * vq + 4 * g);
+          const f32x4 nd = *reinterpret_cast<const f32x4 *>(ndeltas + 32 * qb + 8 * vq + 4 * g);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) { s[nk][v] = 0.f; dp[nk][v] = 0.f; }
+          for (int nk = 0; nk < NK; ++nk)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { s[nk][4 * vq + e] = nl[e]; dp[nk][4 * vq + e] = nd[e]; }
+        }
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-          const Frag qa = QT::nat_frag(qtile, 32 * qb + ln, ks, g);
-          const Frag da = QT::nat_frag(dotile, 32 * qb + ln, ks, g);
+          Frag qa, da;
+          rd.nat2(qblock, QT::BYTES, ks, qa, da);
 #pragma unroll
           for (int nk = 0; nk < NK; ++nk) {
             s[nk] = mma(qa, kf[nk][ks], s[nk]);
-            dp[nk] = mma(da, vf[nk][ks], dp[nk]);
+            dp[nk] = mma(da, rd.nat(vtile + (wave * NK + nk) * BLOCK_BYTES, ks), dp[nk]);
           }
         }
-        // rows of register v: rb + 8*(v/4) + 4*g + v%4
-        f32x4 l2[4], dl[4];
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          l2[vq] = *reinterpret_cast<const f32x4 *>(lse2s + 32 * qb + 8 * vq + 4 * g);
-          dl[vq] = *reinterpret_cast<const f32x4 *>(deltas + 32 * qb + 8 * vq + 4 * g);
-        }
+        // visible iff key <= seg_off + row and row < seg_len, row = rb + 4g + 8*(v/4) + v%4; blocks that
+        // lie wholly below the diagonal and inside the segment (nearly all of them) skip the test
         const bool edge = (wkey0 + 32 * NK - 1 > seg_off + rb) || (rb + 32 > seg_len);
+        if (edge) {
 #pragma unroll
-        for (int nk = 0; nk < NK; ++nk) {
-          const int key = wkey0 + 32 * nk + ln;
-          // visible iff key <= seg_off + row and row < seg_len, row = rb + 4g + 8*(v/4) + v%4
-          const int lo = edge ? key - seg_off - rb - 4 * g : -64;     // need 8*(v/4)+v%4 >= lo
-          const int hi = edge ? seg_len - rb - 4 * g : 64;            // and  8*(v/4)+v%4 <  hi
+          for (int nk = 0; nk < NK; ++nk) {
+            const int lo = wkey0 + 32 * nk + ln - seg_off - rb - 4 * g;   // need 8*(v/4)+v%4 >= lo
+            const int hi = seg_len - rb - 4 * g;                          // and  8*(v/4)+v%4 <  hi
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int rr = 8 * (v >> 2) + (v & 3);
-            float p = exp2_fast(fmaf(s[nk][v], c, -l2[v >> 2][v & 3]));
-            if (rr < lo || rr >= hi) p = 0.f;
-            s[nk][v] = p;
-            dp[nk][v] = p * (dp[nk][v] - dl[v >> 2][v & 3]);
+            for (int v = 0; v < 16; ++v) {
+              const int rr = 8 * (v >> 2) + (v & 3);
+              float p = exp2_fast(s[nk][v] * c);
+              if (rr < lo || rr >= hi) p = 0.f;
+              s[nk][v] = p;
+              dp[nk][v] = p * dp[nk][v];
+            }
           }
+        } else {
+#pragma unroll
+          for (int nk = 0; nk < NK; ++nk)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const float p = exp2_fast(s[nk][v] * c);
+              s[nk][v] = p;
+              dp[nk][v] = p * dp[nk][v];
+            }
         }
 #pragma unroll
         for (int t = 0; t < NSLAB; ++t) {
@@ -323,8 +357,8 @@ __global__ void __launch_bounds__(256) seg_attn_bwd_dkdv_kernel(const AttnArgs a
           }
 #pragma unroll
           for (int db = 0; db < DB; ++db) {
-            const Frag dot = QT::tr_frag(dotile, 32 * qb, t, db, lane);
-            const Frag qtf = QT::tr_frag(qtile, 32 * qb, t, db, lane);
+            Frag qtf, dot;
+            rd.tr2(qblock, QT::BYTES, t, db, qtf, dot);
 #pragma unroll
             for (int nk = 0; nk < NK; ++nk) {
               dv[nk][db] = mma(dot, pf[nk], dv[nk][db]);
@@ -334,7 +368,7 @@ __global__ void __launch_bounds__(256) seg_attn_bwd_dkdv_kernel(const AttnArgs a
         }
       }
     }
-    if (it + 1 < n_it) commit((it + 1) & 1);
+    wait_async_tiles();   // this wave's part of the next tile has landed
     __syncthreads();
   }
 

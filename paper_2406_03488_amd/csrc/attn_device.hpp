@@ -241,6 +241,39 @@ template <int ROWS, int D> struct FragReader<LdsTile<bf16_t, ROWS, D>, bf16_t> {
     s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, r);
   }
+  // The same fragment of two blocks `delta` bytes apart (delta a multiple of 8 KiB in the XOR form): the
+  // swizzled address is computed once and the second read differs in its immediate offset only.
+  S1F_DEV void nat2(lds_addr block, unsigned delta, int ks, bf16x8 &x, bf16x8 &y) const {
+    if (XOR_FORM) {
+      const lds_addr p = (block + nat_x) ^ (unsigned)(32 * ks);
+      x = lds_load<bf16x8>(p);
+      y = lds_load<bf16x8>(p + delta);
+    } else {
+      x = nat(block, ks);
+      y = nat(block + delta, ks);
+    }
+  }
+  S1F_DEV static bf16x8 tr_pair(lds_addr p0, lds_addr p1) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        reinterpret_cast<__attribute__((address_space(3))) s16x4 *>((uintptr_t)p0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        reinterpret_cast<__attribute__((address_space(3))) s16x4 *>((uintptr_t)p1));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+  }
+  S1F_DEV void tr2(lds_addr block, unsigned delta, int t, int db, bf16x8 &x, bf16x8 &y) const {
+    if (XOR_FORM) {
+      const lds_addr q0 = (block + tr_x) ^ (unsigned)(64 * db);
+      const lds_addr q1 = (block + tr_x) ^ (unsigned)((64 * db) ^ (32 + 2048));
+      const unsigned o = t * 16 * ROW_BYTES;
+      x = tr_pair(q0 + o, q1 + o);
+      y = tr_pair(q0 + (o + delta), q1 + (o + delta));
+    } else {
+      x = tr(block, t, db);
+      y = tr(block + delta, t, db);
+    }
+  }
 };
 
 template <int ROWS, int D> struct FragReader<LdsTile<float, ROWS, D>, float> {
@@ -250,6 +283,14 @@ template <int ROWS, int D> struct FragReader<LdsTile<float, ROWS, D>, float> {
   S1F_DEV void init(int lane) { lane_ = lane; }
   S1F_DEV float nat(lds_addr block, int ks) const { return TL::nat_frag(lds_generic(block), lane_ & 31, ks, lane_ >> 5); }
   S1F_DEV float tr(lds_addr block, int t, int db) const { return TL::tr_frag(lds_generic(block), 0, t, db, lane_); }
+  S1F_DEV void nat2(lds_addr block, unsigned delta, int ks, float &x, float &y) const {
+    x = nat(block, ks);
+    y = nat(block + delta, ks);
+  }
+  S1F_DEV void tr2(lds_addr block, unsigned delta, int t, int db, float &x, float &y) const {
+    x = tr(block, t, db);
+    y = tr(block + delta, t, db);
+  }
 };
 
 // Register-staged copy of a [ROWS x D] tile from global memory (row stride in elements) into an
@@ -361,6 +402,73 @@ template <typename T, int ROWS, int D, int NW> struct AsyncTilePair {
   }
 };
 
+// The same copy for two tiles whose rows all lie `row_stride` apart from one wave-uniform base each: the
+// address is (scalar base of the tile) + (32-bit lane offset fixed at init), which keeps one register per
+// instruction instead of a row, a column and a 64-bit pointer.  Rows past `rows_total` re-read the last
+// valid row.  (ROWS - 1) * row_stride * sizeof(T) + row bytes must fit 32 bits.
+template <typename T, int ROWS, int D, int NW> struct AsyncTilePairU {
+  typedef LdsTile<T, ROWS, D> TL;
+  static constexpr int SLOTS = ROWS * TL::RS;
+  static constexpr int PER = 2 * SLOTS / (64 * NW);
+  static constexpr int G = PER < 4 ? PER : 4;
+  static_assert((2 * SLOTS) % (64 * NW) == 0 && SLOTS % (64 * G) == 0, "tiles must split evenly over the waves");
+  static_assert(PER == 1 || PER == 2 || PER % 4 == 0, "instructions are issued in groups of up to four");
+  unsigned voff[PER];   // byte offset of this lane's chunk from the first row of its tile
+
+  S1F_DEV static int slot_row(int wave, int i, int lane) { return (((wave * PER + i) * 64 + lane) % SLOTS) / TL::RS; }
+
+  S1F_DEV void init(int wave, int lane, int64_t row_stride) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int slot = ((wave * PER + i) * 64 + lane) % SLOTS;
+      const int r = slot / TL::RS, pos = slot % TL::RS;
+      int c = pos ^ TL::swz(r);
+      if (TL::CPR < TL::RS && c >= TL::CPR) c &= TL::RS / 2 - 1;
+      voff[i] = (unsigned)((r * row_stride + c * TL::CE) * (int64_t)sizeof(T));
+    }
+  }
+
+  template <int N>
+  S1F_DEV static void issue_group(unsigned dst, const char *tb, unsigned o0, unsigned o1, unsigned o2, unsigned o3) {
+    if (N == 1)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(o0), "s"(tb) : "m0");
+    else if (N == 2)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\t"
+                   "global_load_lds_dwordx4 %2, %4 offset:1024"
+                   : : "s"(dst), "v"(o0), "v"(o1), "s"(tb), "s"(tb - 1024) : "m0");
+    else
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %5\n\t"
+                   "global_load_lds_dwordx4 %2, %6 offset:1024\n\t"
+                   "global_load_lds_dwordx4 %3, %7 offset:2048\n\t"
+                   "global_load_lds_dwordx4 %4, %8 offset:3072"
+                   : : "s"(dst), "v"(o0), "v"(o1), "v"(o2), "v"(o3), "s"(tb), "s"(tb - 1024), "s"(tb - 2048), "s"(tb - 3072)
+                   : "m0");
+  }
+
+  // base0/base1: row 0 of the two tensors (wave-uniform); tile_row0: first row of the tile; stage: LDS
+  // address of the first tile (the second follows it)
+  S1F_DEV void issue(const T *base0, const T *base1, int64_t row_stride, int tile_row0, int rows_total, lds_addr stage,
+                     int wave, int lane) const {
+    unsigned off[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) off[i] = voff[i];
+    if (tile_row0 + ROWS > rows_total) {   // the segment ends inside this tile
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int over = tile_row0 + slot_row(wave, i, lane) - (rows_total - 1);
+        if (over > 0) off[i] -= (unsigned)(over * row_stride * (int64_t)sizeof(T));
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < PER; i += G) {
+      const bool second = (wave * PER + i) * 64 >= SLOTS;     // wave-uniform, the same for the whole group
+      const char *tb = reinterpret_cast<const char *>((second ? base1 : base0) + (int64_t)tile_row0 * row_stride);
+      const unsigned dst = stage + (unsigned)((wave * PER + i) * 1024);
+      issue_group<G>(dst, tb, off[i], off[G > 1 ? i + 1 : i], off[G > 2 ? i + 2 : i], off[G > 2 ? i + 3 : i]);
+    }
+  }
+};
+
 // Wait until every asynchronous tile copy issued by this wave has landed (vmcnt(0), other counters untouched).
 S1F_DEV void wait_async_tiles() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -395,7 +503,9 @@ struct AttnArgs {
   const void *q, *k, *v, *out, *dout;   // out: written by fwd, read by bwd
   void *out_w, *dq;
   float *lse;                            // [batch, Hq, seg_len]
-  float *delta;                          // [batch, Hq, seg_len] workspace (bwd)
+  float *delta;                          // workspace (bwd): two planes [batch, Hq, seg_len], ws_plane floats apart:
+                                         // -lse/scale, then -delta = -rowsum(dO * O)
+  int64_t ws_plane;
   float *dk_acc, *dv_acc;
   int64_t q_sb, q_sh, q_ss;
   int64_t kv_sb, kv_sh, kv_ss;

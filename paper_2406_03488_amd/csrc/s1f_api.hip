@@ -15,12 +15,12 @@ using namespace s1f;
 // K/V tile (BN), rows per staged Q/dO tile (BQ).
 template <typename T> struct Shape;
 //   forward: FNQ query blocks per wave, FKB 32-key blocks per LDS tile, FNW waves, FOCC waves per SIMD
-//   dq:      QNQ, QBN keys per LDS tile, QOCC;   dk/dv: NK key blocks per wave, BQ rows per Q/dO tile
+//   dq:      QNQ, QBN keys per LDS tile, QOCC;   dk/dv: NK key blocks per wave, BQ rows per Q/dO tile, KOCC
 template <> struct Shape<bf16_t> {
-  static constexpr int FNQ = 1, FKB = 2, FNW = 8, FOCC = 2, QNQ = 1, QBN = 32, QOCC = 2, NK = 1, BQ = 64;
+  static constexpr int FNQ = 1, FKB = 2, FNW = 8, FOCC = 2, QNQ = 1, QBN = 32, QOCC = 2, NK = 1, BQ = 32, KOCC = 2;
 };
 template <> struct Shape<float> {
-  static constexpr int FNQ = 1, FKB = 1, FNW = 4, FOCC = 1, QNQ = 1, QBN = 32, QOCC = 1, NK = 1, BQ = 32;
+  static constexpr int FNQ = 1, FKB = 1, FNW = 4, FOCC = 1, QNQ = 1, QBN = 32, QOCC = 1, NK = 1, BQ = 32, KOCC = 1;
 };
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -90,7 +90,7 @@ template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs
   typedef Shape<T> S;
   typedef BwdDkdvCfg<T, D, S::NK, S::BQ> KC;
   const int kv_len = a.seg_off + a.seg_len;
-  return launch(seg_attn_bwd_dkdv_kernel<T, D, S::NK, S::BQ>, (kv_len + KC::BNW - 1) / KC::BNW,
+  return launch(seg_attn_bwd_dkdv_kernel<T, D, S::NK, S::BQ, S::KOCC>, (kv_len + KC::BNW - 1) / KC::BNW,
                 d->n_kv_heads * d->batch, 256, KC::LDS_BYTES, a, st);
 }
 
@@ -131,7 +131,7 @@ extern "C" int s1f_seg_attn_fwd(const s1f_desc *desc, const void *q_seg, const v
 
 extern "C" size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len) {
   if (check_desc(desc) != S1F_OK || check_seg(desc, seg_off, seg_len) != S1F_OK) return 0;
-  return (size_t)desc->batch * (size_t)desc->n_q_heads * (size_t)seg_len * sizeof(float);
+  return 2 * (size_t)desc->batch * (size_t)desc->n_q_heads * (size_t)seg_len * sizeof(float);
 }
 
 namespace {
@@ -150,10 +150,14 @@ int bwd_prepare(const s1f_desc *desc, const void *dout, const void *q_seg, const
   rc = check_seg(desc, seg_off, seg_len);
   if (rc != S1F_OK) return rc;
   if (workspace_bytes < s1f_bwd_workspace_bytes(desc, seg_off, seg_len)) return S1F_EINVAL;
+  // the asynchronous copies address rows of a Q/dO tile and the workspace with 32-bit byte offsets
+  if (desc->q_stride_s >= (int64_t(1) << 23) || desc->batch * desc->n_q_heads * seg_len > (int64_t(1) << 28))
+    return S1F_EUNSUPPORTED;
   *a = make_args(desc, seg_off, seg_len);
   a->q = q_seg; a->k = k_prefix; a->v = v_prefix; a->dout = dout;
   a->lse = const_cast<float *>(lse);
   a->delta = reinterpret_cast<float *>(const_cast<void *>(workspace));
+  a->ws_plane = desc->batch * desc->n_q_heads * seg_len;
   return S1F_OK;
 }
 }  // namespace

@@ -85,7 +85,7 @@ def test_attention_entry_points_validate_before_any_launch():
     assert bwd(_desc(), ws_bytes=4 * 256 * 4 - 1) == 1
     assert bwd(_desc(), seg_off=400, seg_len=200) == 3
     assert bwd(_desc(head_dim=32)) == 2
-    assert lib.s1f_bwd_workspace_bytes(ctypes.byref(_desc()), 0, 256) == 4 * 256 * 4
+    assert lib.s1f_bwd_workspace_bytes(ctypes.byref(_desc()), 0, 256) == 2 * 4 * 256 * 4
     assert lib.s1f_bwd_workspace_bytes(ctypes.byref(_desc()), 500, 256) == 0
     for code in range(0, 6):
         assert isinstance(s1f.strerror(code), str) and s1f.strerror(code)
