@@ -18,24 +18,33 @@ namespace s1f {
 template <typename T, int D, int NQ, int BN> struct BwdDqCfg {
   static constexpr int BM = 128 * NQ;
   typedef LdsTile<T, BN, D> KT;
-  static constexpr int LDS_BYTES = 4 * KT::BYTES;   // {K, V} x 2 buffers
+  static constexpr int STAGE_BYTES = 2 * KT::BYTES;    // K tile, V tile right behind it
+  static constexpr int LDS_BYTES = 2 * STAGE_BYTES;    // two stages
+  static_assert(STAGE_BYTES % 8192 == 0, "stages must keep the 8 KiB alignment of the fragment reader");
 };
 
 // Lane = one query (column ln); keys run over registers.
 //   S^T[key][q]  = K Q^T      A = K (LDS),            B = Q (registers)
 //   dP^T[key][q] = V dO^T     A = V (LDS),            B = dO (registers)
 //   dQ^T[d][q]  += K^T dS^T   A = K read transposed,  B = dS^T slab (registers)
+// The accumulators of the first two products start from the row statistics (-lse/scale and -delta, the
+// same in every register of a lane) so that p = exp2(c * s) and dS = p * dp need no further operand.
+// K/V tiles are copied HBM -> LDS asynchronously, one tile ahead of their use.
 template <typename T, int D, int NQ, int BN, int OCC>
 __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArgs a) {
   typedef Elem<T> E;
   typedef typename E::Frag Frag;
+  typedef BwdDqCfg<T, D, NQ, BN> Cfg;
   typedef LdsTile<T, BN, D> KT;
+  typedef FragReader<KT, T> RD;
   constexpr int EPL = E::EPL, KSTEP = 2 * EPL, NKS = D / KSTEP;
   constexpr int DB = KT::DPAD / 32, NSLAB = 16 / EPL, KB = BN / 32;
   constexpr int BM = 128 * NQ;
+  constexpr int BLOCK_BYTES = 32 * KT::RS * 16;
 
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  extern __shared__ __attribute__((aligned(8192))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int qt, bh;
   decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, qt, bh);
   qt = a.n_tiles - 1 - qt;   // later (heavier) row tiles are scheduled first
@@ -51,8 +60,17 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
   const T *vbase = reinterpret_cast<const T *>(a.v) + b * a.kv_sb + hk * a.kv_sh;
   const int64_t lse_off = ((int64_t)b * a.n_q_heads + h) * seg_len;
 
+  const int last_row = (row0 + BM < seg_len ? row0 + BM : seg_len) - 1;
+  const int n_kt = (seg_off + last_row) / BN + 1;
+  const lds_addr lds0 = to_lds_addr(smem);
+  AsyncTilePairU<T, BN, D, 4> ld;
+  ld.init(wave, lane, a.kv_ss);
+  RD rd;
+  rd.init(lane);
+  ld.issue(kbase, vbase, a.kv_ss, 0, kv_len, lds0, wave, lane);
+
   Frag qf[NQ][NKS], dof[NQ][NKS];
-  float lse2[NQ], delta[NQ];
+  float nl[NQ], nd[NQ];   // -lse/scale and -delta of the lane's rows
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
     const int r = wrow0 + 32 * nq + ln;
@@ -65,11 +83,11 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
       dof[nq][ks] = load_frag_global<T>(dob + off + ks * KSTEP);
       part += frag_dot<T>(dof[nq][ks], load_frag_global<T>(ob + off + ks * KSTEP));
     }
-    delta[nq] = sum_xor32(part);
-    lse2[nq] = a.lse[lse_off + rc] * kLog2e;
+    nd[nq] = -sum_xor32(part);
+    nl[nq] = -a.lse[lse_off + rc] / a.scale;
     if (r < seg_len && g == 0) {   // row statistics for the dK/dV kernel
-      a.delta[lse_off + r] = -a.lse[lse_off + r] / a.scale;
-      a.delta[a.ws_plane + lse_off + r] = -delta[nq];
+      a.delta[lse_off + r] = nl[nq];
+      a.delta[a.ws_plane + lse_off + r] = nd[nq];
     }
   }
 
@@ -81,56 +99,56 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
 #pragma unroll
       for (int v = 0; v < 16; ++v) dq[nq][db][v] = 0.f;
 
-  const int last_row = (row0 + BM < seg_len ? row0 + BM : seg_len) - 1;
-  const int n_kt = (seg_off + last_row) / BN + 1;
   const bool w_active = wrow0 < seg_len;
   const int w_last = (wrow0 + 32 * NQ < seg_len ? wrow0 + 32 * NQ : seg_len) - 1;
   const float c = a.scale * kLog2e;
-
-  TileCopy<T, BN, D, 256> ck, cv;
-  ck.load(kbase, a.kv_ss, kv_len, tid);
-  cv.load(vbase, a.kv_ss, kv_len, tid);
-  ck.store(smem, tid);
-  cv.store(smem + KT::BYTES, tid);
+  wait_async_tiles();
   __syncthreads();
 
   for (int jt = 0; jt < n_kt; ++jt) {
-    const char *kt = smem + (jt & 1) * 2 * KT::BYTES;
-    const char *vt = kt + KT::BYTES;
+    const lds_addr ktile = lds0 + (jt & 1) * Cfg::STAGE_BYTES;   // the V tile lies KT::BYTES behind it
     const int key0 = jt * BN;
-    if (jt + 1 < n_kt) {
-      const int nk0 = key0 + BN;
-      ck.load(kbase + (int64_t)nk0 * a.kv_ss, a.kv_ss, kv_len - nk0, tid);
-      cv.load(vbase + (int64_t)nk0 * a.kv_ss, a.kv_ss, kv_len - nk0, tid);
-    }
+    // the other stage was last read before the barrier that ended the previous iteration
+    if (jt + 1 < n_kt) ld.issue(kbase, vbase, a.kv_ss, key0 + BN, kv_len, lds0 + ((jt + 1) & 1) * Cfg::STAGE_BYTES, wave, lane);
     if (w_active && key0 <= seg_off + w_last) {
-      const bool diag = key0 + BN - 1 > seg_off + wrow0;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
+        const int kb0 = key0 + 32 * kb;
+        if (kb0 > seg_off + w_last) continue;
+        const lds_addr kblock = ktile + kb * BLOCK_BYTES;
         f32x16 s[NQ], dp[NQ];
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) { s[nq][v] = 0.f; dp[nq][v] = 0.f; }
+          for (int v = 0; v < 16; ++v) { s[nq][v] = nl[nq]; dp[nq][v] = nd[nq]; }
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-          const Frag kf = KT::nat_frag(kt, 32 * kb + ln, ks, g);
-          const Frag vf = KT::nat_frag(vt, 32 * kb + ln, ks, g);
+          Frag kf, vf;
+          rd.nat2(kblock, KT::BYTES, ks, kf, vf);
 #pragma unroll
           for (int nq = 0; nq < NQ; ++nq) {
             s[nq] = mma(kf, qf[nq][ks], s[nq]);
             dp[nq] = mma(vf, dof[nq][ks], dp[nq]);
           }
         }
+        // register v holds key kb0 + 8*(v/4) + 4*g + v%4, visible to row r iff key <= seg_off + r; only
+        // the blocks on the diagonal need the test
+        if (kb0 + 31 > seg_off + wrow0) {
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-          const int lim = diag ? seg_off + wrow0 + 32 * nq + ln - (key0 + 32 * kb + 4 * g) : 64;
+          for (int nq = 0; nq < NQ; ++nq) {
+            const int lim = seg_off + wrow0 + 32 * nq + ln - (kb0 + 4 * g);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            float p = exp2_fast(fmaf(s[nq][v], c, -lse2[nq]));
-            if (8 * (v >> 2) + (v & 3) > lim) p = 0.f;
-            s[nq][v] = p * (dp[nq][v] - delta[nq]);   // dS^T
+            for (int v = 0; v < 16; ++v) {
+              float p = exp2_fast(s[nq][v] * c);
+              if (8 * (v >> 2) + (v & 3) > lim) p = 0.f;
+              s[nq][v] = p * dp[nq][v];   // dS^T
+            }
           }
+        } else {
+#pragma unroll
+          for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[nq][v] = exp2_fast(s[nq][v] * c) * dp[nq][v];
         }
 #pragma unroll
         for (int t = 0; t < NSLAB; ++t) {
@@ -139,18 +157,14 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
           for (int nq = 0; nq < NQ; ++nq) dsf[nq] = block_slab<T>(s[nq], t);
 #pragma unroll
           for (int db = 0; db < DB; ++db) {
-            const Frag ktf = KT::tr_frag(kt, 32 * kb, t, db, lane);
+            const Frag ktf = rd.tr(kblock, t, db);
 #pragma unroll
             for (int nq = 0; nq < NQ; ++nq) dq[nq][db] = mma(ktf, dsf[nq], dq[nq][db]);
           }
         }
       }
     }
-    if (jt + 1 < n_kt) {
-      char *nk = smem + ((jt + 1) & 1) * 2 * KT::BYTES;
-      ck.store(nk, tid);
-      cv.store(nk + KT::BYTES, tid);
-    }
+    wait_async_tiles();   // this wave's part of the next tile has landed
     __syncthreads();
   }
 

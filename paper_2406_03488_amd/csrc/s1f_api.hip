@@ -17,7 +17,7 @@ template <typename T> struct Shape;
 //   forward: FNQ query blocks per wave, FKB 32-key blocks per LDS tile, FNW waves, FOCC waves per SIMD
 //   dq:      QNQ, QBN keys per LDS tile, QOCC;   dk/dv: NK key blocks per wave, BQ rows per Q/dO tile, KOCC
 template <> struct Shape<bf16_t> {
-  static constexpr int FNQ = 1, FKB = 2, FNW = 8, FOCC = 2, QNQ = 1, QBN = 32, QOCC = 2, NK = 1, BQ = 32, KOCC = 2;
+  static constexpr int FNQ = 1, FKB = 2, FNW = 8, FOCC = 2, QNQ = 1, QBN = 64, QOCC = 2, NK = 1, BQ = 32, KOCC = 2;
 };
 template <> struct Shape<float> {
   static constexpr int FNQ = 1, FKB = 1, FNW = 4, FOCC = 1, QNQ = 1, QBN = 32, QOCC = 1, NK = 1, BQ = 32, KOCC = 1;
