@@ -13,6 +13,13 @@
 #pragma once
 #include "attn_device.hpp"
 
+// Optional cycle tracing of one wave (development aid, compiled out unless S1F_TRACE is defined).
+#ifdef S1F_TRACE
+#define S1F_BWD_MARK(slot) do { if (trace_on) trace_t[slot] = __builtin_readcyclecounter(); } while (0)
+#else
+#define S1F_BWD_MARK(slot) do { } while (0)
+#endif
+
 namespace s1f {
 
 template <typename T, int D, int NQ, int BN> struct BwdDqCfg {
@@ -192,7 +199,7 @@ template <typename T, int D, int NK, int BQ> struct BwdDkdvCfg {
   typedef LdsTile<T, BQ, D> QT;
   static constexpr int STAGE_BYTES = 2 * QT::BYTES;    // Q tile, dO tile right behind it
   static constexpr int STAT_BYTES = 2 * BQ * 4;        // -lse/scale and -delta of the tile's rows
-  typedef LdsTile<T, BNW, D> VT;                       // the workgroup's V rows
+  typedef PaddedRows<T, BNW, D> VT;                    // the workgroup's V rows
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES + VT::BYTES + 2 * STAT_BYTES;   // two stages, V, statistics
   static_assert(STAGE_BYTES % 8192 == 0, "stages must keep the 8 KiB alignment of the fragment reader");
 };
@@ -217,7 +224,11 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnA
   constexpr int EPL = E::EPL, KSTEP = 2 * EPL, NKS = D / KSTEP;
   constexpr int DB = QT::DPAD / 32, NSLAB = 16 / EPL, QB = BQ / 32;
   constexpr int BLOCK_BYTES = 32 * QT::RS * 16;
+  constexpr int PF = 2;              // operand fragments in flight ahead of their matrix instruction
+  constexpr int NV = NSLAB * DB;     // (slab, d-block) steps of the second pair of products
   static_assert(BQ % 32 == 0 && 2 * BQ <= 256, "query tile");
+  static_assert(NK == 1, "one 32-key block per wave");
+  static_assert(NKS >= PF && NV >= PF, "prefetch ring deeper than the products");
 
   extern __shared__ __attribute__((aligned(8192))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
@@ -252,8 +263,6 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnA
   RD rd;
   rd.init(lane);
   // statistics: lane `lane` of wave w < 2*BQ/64 copies entry 64*w + lane of {-lse/scale [BQ], -delta [BQ]}
-  const int st_idx = wave * 64 + lane, st_row = st_idx % BQ;
-  const unsigned st_plane = (unsigned)((st_idx / BQ) * a.ws_plane);
 
   auto issue = [&](int it) {   // tile `it` (head-major) -> stage it & 1; rows past the segment re-read its last row
     const int hq = hk * a.group + it / per_head;
@@ -262,7 +271,8 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnA
     ld.issue(reinterpret_cast<const T *>(a.q) + qoff, reinterpret_cast<const T *>(a.dout) + qoff, a.q_ss, r0, seg_len,
              lds0 + (it & 1) * Cfg::STAGE_BYTES, wave, lane);
     if (wave < 2 * BQ / 64) {
-      const int rr = r0 + st_row;
+      const int st_idx = wave * 64 + fresh(lane), rr = r0 + st_idx % BQ;
+      const unsigned st_plane = (unsigned)((st_idx / BQ) * a.ws_plane);
       const float *sb = a.delta + ((int64_t)b * a.n_q_heads + hq) * seg_len;     // wave-uniform
       const unsigned so = (st_plane + (unsigned)(rr < seg_len ? rr : seg_len - 1)) * 4u;
       const unsigned dst = stats0 + (unsigned)((it & 1) * Cfg::STAT_BYTES + wave * 256);
@@ -271,39 +281,41 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnA
   };
 
   // V rows of the workgroup's keys -> LDS (rows past the prefix are zero: their products are never stored)
-  {
-    TileCopy<T, Cfg::BNW, D, 256> cv;
-    cv.load(vbase + (int64_t)j0 * a.kv_ss, a.kv_ss, kv_len - j0, tid);
-    cv.store(smem + 2 * Cfg::STAGE_BYTES, tid);
-  }
+  Cfg::VT::template copy<256>(smem + 2 * Cfg::STAGE_BYTES, vbase + (int64_t)j0 * a.kv_ss, a.kv_ss, kv_len - j0, tid);
   // K fragments of the wave's keys stay in registers for the whole kernel.
-  Frag kf[NK][NKS];
-#pragma unroll
-  for (int nk = 0; nk < NK; ++nk) {
-    int key = wkey0 + 32 * nk + ln;
+  Frag kf[NKS];
+  {
+    int key = wkey0 + ln;
     key = key < kv_len ? key : kv_len - 1;     // keys past the prefix are computed on a copy and never stored
     const int64_t off = (int64_t)key * a.kv_ss + EPL * g;
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) kf[nk][ks] = load_frag_global<T>(kbase + off + ks * KSTEP);
+    for (int ks = 0; ks < NKS; ++ks) kf[ks] = load_frag_global<T>(kbase + off + ks * KSTEP);
   }
   issue(0);
-  f32x16 dk[NK][DB], dv[NK][DB];
+  f32x16 dk[DB], dv[DB];
 #pragma unroll
-  for (int nk = 0; nk < NK; ++nk)
+  for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int v = 0; v < 16; ++v) { dk[db][v] = 0.f; dv[db][v] = 0.f; }
 #pragma unroll
-      for (int v = 0; v < 16; ++v) { dk[nk][db][v] = 0.f; dv[nk][db][v] = 0.f; }
+  for (int ks = 0; ks < NKS; ++ks) settle(kf[ks]);
+  const lds_addr vrow = Cfg::VT::lane_base(vtile, wave * 32 + ln, g);   // the lane's row of V
   wait_async_tiles();
   __syncthreads();
 
+#ifdef S1F_TRACE
+  unsigned long long trace_t[8] = {};
+  const bool trace_on = a.trace != nullptr && blockIdx.x == a.trace_wg && tid == a.trace_tid;
+#endif
   for (int it = 0; it < n_it; ++it) {
+    S1F_BWD_MARK(0);
     const lds_addr qtile = lds0 + (it & 1) * Cfg::STAGE_BYTES;
     const float *nlses = stats_lds + (it & 1) * 2 * BQ;   // -lse/scale of the tile's rows, then -delta
     const float *ndeltas = nlses + BQ;
     const int r0 = (qt_first + it % per_head) * BQ;
     // the other stage was last read before the barrier that ended the previous iteration
     if (it + 1 < n_it) issue(it + 1);
+    S1F_BWD_MARK(1);
 
     if (w_active && wkey0 <= seg_off + r0 + BQ - 1) {
 #pragma unroll
@@ -311,85 +323,97 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnA
         const int rb = r0 + 32 * qb;   // first row of this 32-row block
         if (wkey0 > seg_off + rb + 31 || rb >= seg_len) continue;
         const lds_addr qblock = qtile + qb * BLOCK_BYTES;   // the dO block lies QT::BYTES behind it
+        // Operand fragments are read from LDS PF steps ahead of the matrix instruction that consumes them
+        // (the compiler, left alone, reads each one right before its use and exposes the LDS latency on
+        // every step); the scheduling fences keep that order.
+        Frag qa[PF], da[PF], va[PF], tq[PF], tdo[PF];
         // The accumulators start from the row statistics instead of zero (register v holds row
         // rb + 8*(v/4) + 4*g + v%4): s = q.k - lse/scale and dp = dO.v - delta come out of the matrix
         // pipe ready for p = exp2(c*s) and dS = p*dp.
-        f32x16 s[NK], dp[NK];
+        f32x16 s, dp;
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
           const f32x4 nl = *reinterpret_cast<const f32x4 *>(nlses + 32 * qb + 8 * vq + 4 * g);
           const f32x4 nd = *reinterpret_cast<const f32x4 *>(ndeltas + 32 * qb + 8 * vq + 4 * g);
 #pragma unroll
-          for (int nk = 0; nk < NK; ++nk)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { s[nk][4 * vq + e] = nl[e]; dp[nk][4 * vq + e] = nd[e]; }
+          for (int e = 0; e < 4; ++e) { s[4 * vq + e] = nl[e]; dp[4 * vq + e] = nd[e]; }
         }
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+          rd.nat2(qblock, QT::BYTES, i, qa[i], da[i]);
+          va[i] = Cfg::VT::frag(vrow, i);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-          Frag qa, da;
-          rd.nat2(qblock, QT::BYTES, ks, qa, da);
-#pragma unroll
-          for (int nk = 0; nk < NK; ++nk) {
-            s[nk] = mma(qa, kf[nk][ks], s[nk]);
-            dp[nk] = mma(da, rd.nat(vtile + (wave * NK + nk) * BLOCK_BYTES, ks), dp[nk]);
+          s = mma(qa[ks % PF], kf[ks], s);
+          dp = mma(da[ks % PF], va[ks % PF], dp);
+          if (ks + PF < NKS) {
+            rd.nat2(qblock, QT::BYTES, ks + PF, qa[ks % PF], da[ks % PF]);
+            va[ks % PF] = Cfg::VT::frag(vrow, ks + PF);
+          } else {   // the rings drain: start on the operands of the second pair of products
+            const int i = ks + PF - NKS;
+            rd.tr2(qblock, QT::BYTES, i / DB, i % DB, tq[i], tdo[i]);
           }
+          __builtin_amdgcn_sched_barrier(0);
         }
+        S1F_BWD_MARK(2);
         // visible iff key <= seg_off + row and row < seg_len, row = rb + 4g + 8*(v/4) + v%4; blocks that
         // lie wholly below the diagonal and inside the segment (nearly all of them) skip the test
-        const bool edge = (wkey0 + 32 * NK - 1 > seg_off + rb) || (rb + 32 > seg_len);
+        const bool edge = (wkey0 + 31 > seg_off + rb) || (rb + 32 > seg_len);
         if (edge) {
+          const int fl = fresh(lane), fg = fl >> 5;
+          const int lo = wkey0 + (fl & 31) - seg_off - rb - 4 * fg;   // need 8*(v/4)+v%4 >= lo
+          const int hi = seg_len - rb - 4 * fg;                       // and  8*(v/4)+v%4 <  hi
 #pragma unroll
-          for (int nk = 0; nk < NK; ++nk) {
-            const int lo = wkey0 + 32 * nk + ln - seg_off - rb - 4 * g;   // need 8*(v/4)+v%4 >= lo
-            const int hi = seg_len - rb - 4 * g;                          // and  8*(v/4)+v%4 <  hi
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int rr = 8 * (v >> 2) + (v & 3);
-              float p = exp2_fast(s[nk][v] * c);
-              if (rr < lo || rr >= hi) p = 0.f;
-              s[nk][v] = p;
-              dp[nk][v] = p * dp[nk][v];
-            }
+          for (int v = 0; v < 16; ++v) {
+            const int rr = 8 * (v >> 2) + (v & 3);
+            float p = exp2_fast(s[v] * c);
+            if (rr < lo || rr >= hi) p = 0.f;
+            s[v] = p;
+            dp[v] = p * dp[v];
           }
         } else {
 #pragma unroll
-          for (int nk = 0; nk < NK; ++nk)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const float p = exp2_fast(s[nk][v] * c);
-              s[nk][v] = p;
-              dp[nk][v] = p * dp[nk][v];
-            }
+          for (int v = 0; v < 16; ++v) {
+            const float p = exp2_fast(s[v] * c);
+            s[v] = p;
+            dp[v] = p * dp[v];
+          }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        S1F_BWD_MARK(3);
+        Frag pf, dsf;
 #pragma unroll
-        for (int t = 0; t < NSLAB; ++t) {
-          Frag pf[NK], dsf[NK];
-#pragma unroll
-          for (int nk = 0; nk < NK; ++nk) {
-            pf[nk] = block_slab<T>(s[nk], t);
-            dsf[nk] = block_slab<T>(dp[nk], t);
+        for (int i = 0; i < NV; ++i) {
+          const int t = i / DB, db = i % DB;
+          if (db == 0) {
+            pf = block_slab<T>(s, t);
+            dsf = block_slab<T>(dp, t);
           }
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            Frag qtf, dot;
-            rd.tr2(qblock, QT::BYTES, t, db, qtf, dot);
-#pragma unroll
-            for (int nk = 0; nk < NK; ++nk) {
-              dv[nk][db] = mma(dot, pf[nk], dv[nk][db]);
-              dk[nk][db] = mma(qtf, dsf[nk], dk[nk][db]);
-            }
-          }
+          dv[db] = mma(tdo[i % PF], pf, dv[db]);
+          dk[db] = mma(tq[i % PF], dsf, dk[db]);
+          if (i + PF < NV) rd.tr2(qblock, QT::BYTES, (i + PF) / DB, (i + PF) % DB, tq[i % PF], tdo[i % PF]);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
+    S1F_BWD_MARK(4);
     wait_async_tiles();   // this wave's part of the next tile has landed
+    S1F_BWD_MARK(5);
     __syncthreads();
+#ifdef S1F_TRACE
+    S1F_BWD_MARK(6);
+    if (trace_on && it >= 20 && it < 84) {
+      unsigned long long *dst = a.trace + (size_t)(it - 20) * 8;
+      for (int i = 0; i < 7; ++i) dst[i] = trace_t[i];
+    }
+#endif
   }
 
   float *dkb = a.dk_acc + kvoff, *dvb = a.dv_acc + kvoff;
-#pragma unroll
-  for (int nk = 0; nk < NK; ++nk) {
-    const int key = wkey0 + 32 * nk + ln;
+  {
+    const int key = wkey0 + ln;
     if (key < kv_len) {
       float *dkr = dkb + (int64_t)key * a.kv_ss, *dvr = dvb + (int64_t)key * a.kv_ss;
 #pragma unroll
@@ -401,8 +425,8 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnA
             f32x4 x = *reinterpret_cast<f32x4 *>(dkr + d0), y = *reinterpret_cast<f32x4 *>(dvr + d0);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              x[e] += dk[nk][db][4 * vq + e] * a.scale;
-              y[e] += dv[nk][db][4 * vq + e];
+              x[e] += dk[db][4 * vq + e] * a.scale;
+              y[e] += dv[db][4 * vq + e];
             }
             *reinterpret_cast<f32x4 *>(dkr + d0) = x;
             *reinterpret_cast<f32x4 *>(dvr + d0) = y;

@@ -182,6 +182,14 @@ S1F_DEV const char *lds_generic(lds_addr a) {
   return (const char *)reinterpret_cast<const __attribute__((address_space(3))) char *>((uintptr_t)a);
 }
 
+// Returns x through an opaque barrier: values derived from the result are recomputed where they are used
+// instead of being kept in registers across a loop (the kernels run at the register limit of two waves
+// per SIMD, and the compiler otherwise hoists every loop-invariant lane value it can find).
+S1F_DEV int fresh(int x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
 // Reads operand fragments of 32-row blocks out of an LdsTile.  The swizzle depends on the row modulo 16
 // only, so for a block starting at a multiple of 16 rows every address is (block base: uniform) combined
 // with a lane part computed once, here.  `block` below is the LDS address of the block's first row.
@@ -455,7 +463,7 @@ template <typename T, int ROWS, int D, int NW> struct AsyncTilePairU {
     if (tile_row0 + ROWS > rows_total) {   // the segment ends inside this tile
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
-        const int over = tile_row0 + slot_row(wave, i, lane) - (rows_total - 1);
+        const int over = tile_row0 + slot_row(wave, i, fresh(lane)) - (rows_total - 1);
         if (over > 0) off[i] -= (unsigned)(over * row_stride * (int64_t)sizeof(T));
       }
     }
@@ -468,6 +476,41 @@ template <typename T, int ROWS, int D, int NW> struct AsyncTilePairU {
     }
   }
 };
+
+// A [ROWS x D] tile in LDS whose rows are 16 bytes longer than their data: lane ln reading row ln (both
+// half-waves, one 16-byte chunk apart) is bank-conflict free without a swizzle, and the fragments along
+// D of one lane differ by a compile-time offset only (one address register, no per-fragment arithmetic).
+// Used for operands that are copied once through registers and never read transposed.
+template <typename T, int ROWS, int D> struct PaddedRows {
+  static constexpr int CE = Elem<T>::CE, CPR = D / CE;
+  static constexpr int ROW_BYTES = CPR * 16 + 16;
+  static constexpr int BYTES = ROWS * ROW_BYTES;
+  // rows [0, rows_valid) of `base` (row stride in elements) -> tile; the rest is zero-filled
+  template <int NT> S1F_DEV static void copy(char *tile, const T *base, int64_t row_stride, int rows_valid, int tid) {
+    constexpr int TOTAL = ROWS * CPR;
+    static_assert(TOTAL % NT == 0, "tile must split evenly over the threads");
+#pragma unroll
+    for (int i = 0; i < TOTAL / NT; ++i) {
+      const int id = tid + i * NT, r = id / CPR, c = id % CPR;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (r < rows_valid) v = *reinterpret_cast<const u32x4 *>(base + (int64_t)r * row_stride + c * CE);
+      *reinterpret_cast<u32x4 *>(tile + r * ROW_BYTES + c * 16) = v;
+    }
+  }
+  // address of the fragment (row, contraction step 0) of lane (ln, g); step ks lies ks * KSTEP * sizeof(T) further
+  S1F_DEV static lds_addr lane_base(lds_addr tile, int row, int g) {
+    return tile + (unsigned)(row * ROW_BYTES + g * Elem<T>::EPL * (int)sizeof(T));
+  }
+  S1F_DEV static typename Elem<T>::Frag frag(lds_addr lane_base_addr, int ks) {
+    return lds_load<typename Elem<T>::Frag>(lane_base_addr + (unsigned)(ks * 2 * Elem<T>::EPL * (int)sizeof(T)));
+  }
+};
+
+// Marks a value loaded from memory as used here.  The compiler then waits for the load at this point
+// instead of at the first real use; kernels call it on operands fetched before their main loop, whose
+// first use inside the loop would otherwise put a vmcnt wait there that also waits (on every iteration)
+// for the asynchronous tile copies in flight.
+template <typename V> S1F_DEV void settle(V &v) { asm volatile("" : "+v"(v)); }
 
 // Wait until every asynchronous tile copy issued by this wave has landed (vmcnt(0), other counters untouched).
 S1F_DEV void wait_async_tiles() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
