@@ -194,14 +194,22 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
   }
 }
 
-template <typename T, int D, int NK, int BQ> struct BwdDkdvCfg {
-  static constexpr int BNW = 128 * NK;                 // keys per workgroup
+// dK/dV kernel.  NW waves of 32 keys each; Q/dO tiles of 32 rows travel through a ring of NST LDS stages.
+// DIST: a tile's copy is issued DIST iterations before the iteration that consumes it.
+// LAG:  with LAG = 1 the upper half of the waves runs one phase behind the lower half (see the kernel), which
+// keeps each tile alive for one more iteration.
+template <typename T, int D, int NW, int DIST, int LAG> struct BwdDkdvCfg {
+  static constexpr int BQ = 32;                        // rows per Q/dO tile
+  static constexpr int BNW = 32 * NW;                  // keys per workgroup
+  static constexpr int THREADS = 64 * NW;
+  static constexpr int NST = DIST + LAG + 1;           // ring stages
   typedef LdsTile<T, BQ, D> QT;
   static constexpr int STAGE_BYTES = 2 * QT::BYTES;    // Q tile, dO tile right behind it
   static constexpr int STAT_BYTES = 2 * BQ * 4;        // -lse/scale and -delta of the tile's rows
   typedef PaddedRows<T, BNW, D> VT;                    // the workgroup's V rows
-  static constexpr int LDS_BYTES = 2 * STAGE_BYTES + VT::BYTES + 2 * STAT_BYTES;   // two stages, V, statistics
+  static constexpr int LDS_BYTES = NST * STAGE_BYTES + VT::BYTES + NST * STAT_BYTES;   // stages, V, statistics
   static_assert(STAGE_BYTES % 8192 == 0, "stages must keep the 8 KiB alignment of the fragment reader");
+  static_assert(DIST >= 1 && LAG >= 0 && LAG <= 1 && NW % 4 == 0, "schedule");
 };
 
 // Lane = one key (column ln); queries run over registers.
@@ -210,25 +218,27 @@ template <typename T, int D, int NK, int BQ> struct BwdDkdvCfg {
 //   dV^T[d][key] += dO^T P     A = dO read transposed,   B = P slab (registers)
 //   dK^T[d][key] += Q^T dS     A = Q read transposed,    B = dS slab (registers)
 // The wave's K fragments, its dK and dV accumulators and the block's S and dP fill the register budget of
-// two waves per SIMD; its V rows are therefore read from LDS (copied there once).
-// Q/dO tiles and their row statistics are copied HBM -> LDS asynchronously (no staging registers) one tile
-// ahead of their use, so that two workgroups fit on a compute unit and fill each other's barrier and
-// latency gaps.
-template <typename T, int D, int NK, int BQ, int OCC = 1>
-__global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnArgs a) {
+// two waves per SIMD; its V rows are therefore read from LDS (copied there once, in padded rows).
+// Q/dO tiles and their row statistics are copied HBM -> LDS asynchronously (no staging registers).
+//
+// A wave's work on one tile has three phases: B (S and dP on the matrix pipe), C (exp and dS on the vector
+// pipe), D (dV and dK on the matrix pipe).  The two waves that share a SIMD belong to the two halves of the
+// workgroup; with LAG = 1 the upper half runs the sequence one phase late (C and D of the previous tile,
+// then B of the current one), so that between two barriers one wave's vector phase meets the other's matrix
+// phases instead of both queueing for the same pipe.
+template <typename T, int D, int NW, int DIST, int LAG, int WGS = 1>   // WGS: workgroups meant to share a compute unit
+__global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kernel(const AttnArgs a) {
   typedef Elem<T> E;
   typedef typename E::Frag Frag;
-  typedef BwdDkdvCfg<T, D, NK, BQ> Cfg;
-  typedef LdsTile<T, BQ, D> QT;
+  typedef BwdDkdvCfg<T, D, NW, DIST, LAG> Cfg;
+  typedef typename Cfg::QT QT;
   typedef FragReader<QT, T> RD;
   constexpr int EPL = E::EPL, KSTEP = 2 * EPL, NKS = D / KSTEP;
-  constexpr int DB = QT::DPAD / 32, NSLAB = 16 / EPL, QB = BQ / 32;
-  constexpr int BLOCK_BYTES = 32 * QT::RS * 16;
-  constexpr int PF = 2;              // operand fragments in flight ahead of their matrix instruction
+  constexpr int DB = QT::DPAD / 32, NSLAB = 16 / EPL, BQ = Cfg::BQ, NST = Cfg::NST;
+  constexpr int PF = 2;              // steps by which operand fragments are read ahead in phase B ...
+  constexpr int PFD = 2;             // ... and in phase D (deeper rings spill at two waves per SIMD and run slower)
   constexpr int NV = NSLAB * DB;     // (slab, d-block) steps of the second pair of products
-  static_assert(BQ % 32 == 0 && 2 * BQ <= 256, "query tile");
-  static_assert(NK == 1, "one 32-key block per wave");
-  static_assert(NKS >= PF && NV >= PF, "prefetch ring deeper than the products");
+  static_assert(NKS >= PF && NV >= PFD && PFD >= PF, "prefetch ring deeper than the products");
 
   extern __shared__ __attribute__((aligned(8192))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
@@ -239,13 +249,14 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnA
   const int hk = bh % n_kv_heads, b = bh / n_kv_heads;
   const int seg_off = a.seg_off, seg_len = a.seg_len, kv_len = seg_off + seg_len;
   const int j0 = kt * Cfg::BNW;                    // first key of the workgroup
-  const int wkey0 = j0 + wave * 32 * NK;           // first key of the wave
+  const int wkey0 = j0 + wave * 32;                // first key of the wave
 
   const int64_t kvoff = b * a.kv_sb + hk * a.kv_sh;
   const T *kbase = reinterpret_cast<const T *>(a.k) + kvoff;
   const T *vbase = reinterpret_cast<const T *>(a.v) + kvoff;
 
-  // First query row that can see any key of this workgroup, and the tile holding it.
+  // First query row that can see any key of this workgroup, and the tile holding it.  Iteration `it` covers
+  // tile qt_first + it % per_head of query head hk * group + it / per_head.
   const int r_first = j0 > seg_off ? j0 - seg_off : 0;
   const int qt_first = r_first / BQ;
   const int n_qt = (seg_len + BQ - 1) / BQ;
@@ -255,33 +266,38 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnA
   const bool w_active = wkey0 < kv_len;
 
   const lds_addr lds0 = to_lds_addr(smem);
-  const lds_addr vtile = lds0 + 2 * Cfg::STAGE_BYTES;
+  const lds_addr vtile = lds0 + NST * Cfg::STAGE_BYTES;
   const lds_addr stats0 = vtile + Cfg::VT::BYTES;
-  const float *stats_lds = reinterpret_cast<const float *>(smem + 2 * Cfg::STAGE_BYTES + Cfg::VT::BYTES);
-  AsyncTilePairU<T, BQ, D, 4> ld;
+  AsyncTilePairU<T, BQ, D, NW> ld;
   ld.init(wave, lane, a.q_ss);
   RD rd;
   rd.init(lane);
-  // statistics: lane `lane` of wave w < 2*BQ/64 copies entry 64*w + lane of {-lse/scale [BQ], -delta [BQ]}
 
-  auto issue = [&](int it) {   // tile `it` (head-major) -> stage it & 1; rows past the segment re-read its last row
-    const int hq = hk * a.group + it / per_head;
-    const int r0 = (qt_first + it % per_head) * BQ;
-    const int64_t qoff = b * a.q_sb + hq * a.q_sh;
-    ld.issue(reinterpret_cast<const T *>(a.q) + qoff, reinterpret_cast<const T *>(a.dout) + qoff, a.q_ss, r0, seg_len,
-             lds0 + (it & 1) * Cfg::STAGE_BYTES, wave, lane);
-    if (wave < 2 * BQ / 64) {
-      const int st_idx = wave * 64 + fresh(lane), rr = r0 + st_idx % BQ;
+  // Tile cursors (row offset of the tile, its query head, its ring stage), advanced once per iteration.
+  struct Cursor {
+    int r0, hq, stage;
+  };
+  auto advance = [&](Cursor &t) {
+    t.r0 += BQ;
+    if (t.r0 >= n_qt * BQ) { t.r0 = qt_first * BQ; ++t.hq; }
+    t.stage = t.stage + 1 == NST ? 0 : t.stage + 1;
+  };
+  auto issue = [&](const Cursor &t) {   // rows past the segment re-read its last row
+    const int64_t qoff = b * a.q_sb + t.hq * a.q_sh;
+    ld.issue(reinterpret_cast<const T *>(a.q) + qoff, reinterpret_cast<const T *>(a.dout) + qoff, a.q_ss, t.r0, seg_len,
+             lds0 + t.stage * Cfg::STAGE_BYTES, wave, lane);
+    if (wave < 2 * BQ / 64) {   // lane `lane` copies entry 64*wave + lane of {-lse/scale [BQ], -delta [BQ]}
+      const int st_idx = wave * 64 + fresh(lane), rr = t.r0 + st_idx % BQ;
       const unsigned st_plane = (unsigned)((st_idx / BQ) * a.ws_plane);
-      const float *sb = a.delta + ((int64_t)b * a.n_q_heads + hq) * seg_len;     // wave-uniform
+      const float *sb = a.delta + ((int64_t)b * a.n_q_heads + t.hq) * seg_len;     // wave-uniform
       const unsigned so = (st_plane + (unsigned)(rr < seg_len ? rr : seg_len - 1)) * 4u;
-      const unsigned dst = stats0 + (unsigned)((it & 1) * Cfg::STAT_BYTES + wave * 256);
+      const unsigned dst = stats0 + (unsigned)(t.stage * Cfg::STAT_BYTES + wave * 256);
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(so), "s"(sb) : "m0");
     }
   };
 
   // V rows of the workgroup's keys -> LDS (rows past the prefix are zero: their products are never stored)
-  Cfg::VT::template copy<256>(smem + 2 * Cfg::STAGE_BYTES, vbase + (int64_t)j0 * a.kv_ss, a.kv_ss, kv_len - j0, tid);
+  Cfg::VT::template copy<Cfg::THREADS>(smem + NST * Cfg::STAGE_BYTES, vbase + (int64_t)j0 * a.kv_ss, a.kv_ss, kv_len - j0, tid);
   // K fragments of the wave's keys stay in registers for the whole kernel.
   Frag kf[NKS];
   {
@@ -291,7 +307,11 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnA
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) kf[ks] = load_frag_global<T>(kbase + off + ks * KSTEP);
   }
-  issue(0);
+  Cursor t_iss = {qt_first * BQ, hk * a.group, 0};   // next tile to copy
+  for (int i = 0; i < DIST; ++i) {
+    if (i < n_it) issue(t_iss);
+    advance(t_iss);
+  }
   f32x16 dk[DB], dv[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
@@ -303,112 +323,132 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dkdv_kernel(const AttnA
   wait_async_tiles();
   __syncthreads();
 
-#ifdef S1F_TRACE
-  unsigned long long trace_t[8] = {};
-  const bool trace_on = a.trace != nullptr && blockIdx.x == a.trace_wg && tid == a.trace_tid;
-#endif
-  for (int it = 0; it < n_it; ++it) {
-    S1F_BWD_MARK(0);
-    const lds_addr qtile = lds0 + (it & 1) * Cfg::STAGE_BYTES;
-    const float *nlses = stats_lds + (it & 1) * 2 * BQ;   // -lse/scale of the tile's rows, then -delta
-    const float *ndeltas = nlses + BQ;
-    const int r0 = (qt_first + it % per_head) * BQ;
-    // the other stage was last read before the barrier that ended the previous iteration
-    if (it + 1 < n_it) issue(it + 1);
-    S1F_BWD_MARK(1);
+  // State of the tile in flight.  Operand fragments are read from LDS PF steps ahead of the matrix
+  // instruction that consumes them (the compiler, left alone, reads each one right before its use and
+  // exposes the LDS latency on every step); the scheduling fences keep that order.
+  struct State {
+    f32x16 s, dp;
+    Frag qa[PF], da[PF], va[PF], tq[PFD], tdo[PFD];
+  };
+  auto active = [&](const Cursor &t) { return w_active && wkey0 <= seg_off + t.r0 + 31; };
 
-    if (w_active && wkey0 <= seg_off + r0 + BQ - 1) {
+  // Phase B: the accumulators start from the row statistics instead of zero (register v holds row
+  // r0 + 8*(v/4) + 4*g + v%4), so that s = q.k - lse/scale and dp = dO.v - delta come out of the matrix
+  // pipe ready for p = exp2(c*s) and dS = p*dp.
+  auto phase_b = [&](State &z, const Cursor &t) {
+    const lds_addr qblock = lds0 + t.stage * Cfg::STAGE_BYTES;   // the dO block lies QT::BYTES behind it
+    const lds_addr st = stats0 + (unsigned)(t.stage * Cfg::STAT_BYTES + 16 * g);
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int rb = r0 + 32 * qb;   // first row of this 32-row block
-        if (wkey0 > seg_off + rb + 31 || rb >= seg_len) continue;
-        const lds_addr qblock = qtile + qb * BLOCK_BYTES;   // the dO block lies QT::BYTES behind it
-        // Operand fragments are read from LDS PF steps ahead of the matrix instruction that consumes them
-        // (the compiler, left alone, reads each one right before its use and exposes the LDS latency on
-        // every step); the scheduling fences keep that order.
-        Frag qa[PF], da[PF], va[PF], tq[PF], tdo[PF];
-        // The accumulators start from the row statistics instead of zero (register v holds row
-        // rb + 8*(v/4) + 4*g + v%4): s = q.k - lse/scale and dp = dO.v - delta come out of the matrix
-        // pipe ready for p = exp2(c*s) and dS = p*dp.
-        f32x16 s, dp;
+    for (int vq = 0; vq < 4; ++vq) {
+      const f32x4 nl = lds_load<f32x4>(st + 32 * vq);
+      const f32x4 nd = lds_load<f32x4>(st + 4 * BQ + 32 * vq);
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          const f32x4 nl = *reinterpret_cast<const f32x4 *>(nlses + 32 * qb + 8 * vq + 4 * g);
-          const f32x4 nd = *reinterpret_cast<const f32x4 *>(ndeltas + 32 * qb + 8 * vq + 4 * g);
+      for (int e = 0; e < 4; ++e) { z.s[4 * vq + e] = nl[e]; z.dp[4 * vq + e] = nd[e]; }
+    }
 #pragma unroll
-          for (int e = 0; e < 4; ++e) { s[4 * vq + e] = nl[e]; dp[4 * vq + e] = nd[e]; }
-        }
+    for (int i = 0; i < PF; ++i) {
+      rd.nat2(qblock, QT::BYTES, i, z.qa[i], z.da[i]);
+      z.va[i] = Cfg::VT::frag(vrow, i);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < PF; ++i) {
-          rd.nat2(qblock, QT::BYTES, i, qa[i], da[i]);
-          va[i] = Cfg::VT::frag(vrow, i);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+    for (int ks = 0; ks < NKS; ++ks) {
+      z.s = mma(z.qa[ks % PF], kf[ks], z.s);
+      z.dp = mma(z.da[ks % PF], z.va[ks % PF], z.dp);
+      if (ks + PF < NKS) {
+        rd.nat2(qblock, QT::BYTES, ks + PF, z.qa[ks % PF], z.da[ks % PF]);
+        z.va[ks % PF] = Cfg::VT::frag(vrow, ks + PF);
+      } else {   // the rings drain: start on the operands of phase D
+        const int i = ks + PF - NKS;
+        rd.tr2(qblock, QT::BYTES, i / DB, i % DB, z.tq[i], z.tdo[i]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // Phase C.  Visible iff key <= seg_off + row and row < seg_len, row = r0 + 4g + 8*(v/4) + v%4; blocks that
+  // lie wholly below the diagonal and inside the segment (nearly all of them) skip the test.
+  auto phase_c = [&](State &z, const Cursor &t) {
+    const lds_addr qblock = lds0 + t.stage * Cfg::STAGE_BYTES;
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-          s = mma(qa[ks % PF], kf[ks], s);
-          dp = mma(da[ks % PF], va[ks % PF], dp);
-          if (ks + PF < NKS) {
-            rd.nat2(qblock, QT::BYTES, ks + PF, qa[ks % PF], da[ks % PF]);
-            va[ks % PF] = Cfg::VT::frag(vrow, ks + PF);
-          } else {   // the rings drain: start on the operands of the second pair of products
-            const int i = ks + PF - NKS;
-            rd.tr2(qblock, QT::BYTES, i / DB, i % DB, tq[i], tdo[i]);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        S1F_BWD_MARK(2);
-        // visible iff key <= seg_off + row and row < seg_len, row = rb + 4g + 8*(v/4) + v%4; blocks that
-        // lie wholly below the diagonal and inside the segment (nearly all of them) skip the test
-        const bool edge = (wkey0 + 31 > seg_off + rb) || (rb + 32 > seg_len);
-        if (edge) {
-          const int fl = fresh(lane), fg = fl >> 5;
-          const int lo = wkey0 + (fl & 31) - seg_off - rb - 4 * fg;   // need 8*(v/4)+v%4 >= lo
-          const int hi = seg_len - rb - 4 * fg;                       // and  8*(v/4)+v%4 <  hi
+    for (int i = PF; i < PFD; ++i) rd.tr2(qblock, QT::BYTES, i / DB, i % DB, z.tq[i], z.tdo[i]);   // rest of phase D's ring
+    __builtin_amdgcn_sched_barrier(0);
+    const bool edge = (wkey0 + 31 > seg_off + t.r0) || (t.r0 + 32 > seg_len);
+    if (edge) {
+      const int fl = fresh(lane), fg = fl >> 5;
+      const int lo = wkey0 + (fl & 31) - seg_off - t.r0 - 4 * fg;   // need 8*(v/4)+v%4 >= lo
+      const int hi = seg_len - t.r0 - 4 * fg;                       // and  8*(v/4)+v%4 <  hi
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int rr = 8 * (v >> 2) + (v & 3);
-            float p = exp2_fast(s[v] * c);
-            if (rr < lo || rr >= hi) p = 0.f;
-            s[v] = p;
-            dp[v] = p * dp[v];
-          }
-        } else {
+      for (int v = 0; v < 16; ++v) {
+        const int rr = 8 * (v >> 2) + (v & 3);
+        float p = exp2_fast(z.s[v] * c);
+        if (rr < lo || rr >= hi) p = 0.f;
+        z.s[v] = p;
+        z.dp[v] = p * z.dp[v];
+      }
+    } else {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float p = exp2_fast(s[v] * c);
-            s[v] = p;
-            dp[v] = p * dp[v];
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        S1F_BWD_MARK(3);
-        Frag pf, dsf;
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-          const int t = i / DB, db = i % DB;
-          if (db == 0) {
-            pf = block_slab<T>(s, t);
-            dsf = block_slab<T>(dp, t);
-          }
-          dv[db] = mma(tdo[i % PF], pf, dv[db]);
-          dk[db] = mma(tq[i % PF], dsf, dk[db]);
-          if (i + PF < NV) rd.tr2(qblock, QT::BYTES, (i + PF) / DB, (i + PF) % DB, tq[i % PF], tdo[i % PF]);
-          __builtin_amdgcn_sched_barrier(0);
-        }
+      for (int v = 0; v < 16; ++v) {
+        const float p = exp2_fast(z.s[v] * c);
+        z.s[v] = p;
+        z.dp[v] = p * z.dp[v];
       }
     }
-    S1F_BWD_MARK(4);
-    wait_async_tiles();   // this wave's part of the next tile has landed
-    S1F_BWD_MARK(5);
-    __syncthreads();
-#ifdef S1F_TRACE
-    S1F_BWD_MARK(6);
-    if (trace_on && it >= 20 && it < 84) {
-      unsigned long long *dst = a.trace + (size_t)(it - 20) * 8;
-      for (int i = 0; i < 7; ++i) dst[i] = trace_t[i];
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto phase_d = [&](State &z, const Cursor &t) {
+    const lds_addr qblock = lds0 + t.stage * Cfg::STAGE_BYTES;
+    Frag pf, dsf;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int sl = i / DB, db = i % DB;
+      if (db == 0) {
+        pf = block_slab<T>(z.s, sl);
+        dsf = block_slab<T>(z.dp, sl);
+      }
+      dv[db] = mma(z.tdo[i % PFD], pf, dv[db]);
+      dk[db] = mma(z.tq[i % PFD], dsf, dk[db]);
+      if (i + PFD < NV) rd.tr2(qblock, QT::BYTES, (i + PFD) / DB, (i + PFD) % DB, z.tq[i % PFD], z.tdo[i % PFD]);
+      __builtin_amdgcn_sched_barrier(0);
     }
-#endif
+  };
+
+  Cursor cur = {qt_first * BQ, hk * a.group, 0};   // tile of the current iteration
+  const bool late = LAG > 0 && wave >= NW / 2;
+  if (!late) {
+    for (int it = 0; it < n_it; ++it) {
+      // the stage this copy overwrites was last read before the barrier that ended the previous iteration
+      if (it + DIST < n_it) issue(t_iss);
+      advance(t_iss);
+      if (active(cur)) {
+        State z;
+        phase_b(z, cur);
+        phase_c(z, cur);
+        phase_d(z, cur);
+      }
+      advance(cur);
+      wait_async_tiles();   // this wave's part of tile it+DIST has landed
+      __syncthreads();
+    }
+  } else {
+    State z;
+    Cursor prev = cur;
+    for (int it = 0; it < n_it; ++it) {
+      if (it + DIST < n_it) issue(t_iss);
+      advance(t_iss);
+      if (it > 0 && active(prev)) {
+        phase_c(z, prev);
+        phase_d(z, prev);
+      }
+      if (active(cur)) phase_b(z, cur);
+      prev = cur;
+      advance(cur);
+      wait_async_tiles();
+      __syncthreads();
+    }
+    if (active(prev)) {
+      phase_c(z, prev);
+      phase_d(z, prev);
+    }
   }
 
   float *dkb = a.dk_acc + kvoff, *dvb = a.dv_acc + kvoff;

@@ -189,6 +189,11 @@ S1F_DEV int fresh(int x) {
   asm volatile("" : "+v"(x));
   return x;
 }
+// The same for a wave-uniform value (stays in a scalar register).
+S1F_DEV unsigned fresh_uniform(unsigned x) {
+  asm volatile("" : "+s"(x));
+  return x;
+}
 
 // Reads operand fragments of 32-row blocks out of an LdsTile.  The swizzle depends on the row modulo 16
 // only, so for a block starting at a multiple of 16 rows every address is (block base: uniform) combined
@@ -457,22 +462,32 @@ template <typename T, int ROWS, int D, int NW> struct AsyncTilePairU {
   // address of the first tile (the second follows it)
   S1F_DEV void issue(const T *base0, const T *base1, int64_t row_stride, int tile_row0, int rows_total, lds_addr stage,
                      int wave, int lane) const {
-    unsigned off[PER];
 #pragma unroll
-    for (int i = 0; i < PER; ++i) off[i] = voff[i];
-    if (tile_row0 + ROWS > rows_total) {   // the segment ends inside this tile
+    for (int p = 0; p < PARTS; ++p) issue_part(p, base0, base1, row_stride, tile_row0, rows_total, stage, wave, lane);
+  }
+  // One group of up to four of the wave's instructions (0 <= part < PARTS).  Issuing the parts at different
+  // points of a tile's computation keeps a wave from queueing behind the copies of its whole workgroup.
+  static constexpr int PARTS = PER / G;
+  S1F_DEV void issue_part(int part, const T *base0, const T *base1, int64_t row_stride, int tile_row0, int rows_total,
+                          lds_addr stage, int wave, int lane) const {
 #pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        const int over = tile_row0 + slot_row(wave, i, fresh(lane)) - (rows_total - 1);
-        if (over > 0) off[i] -= (unsigned)(over * row_stride * (int64_t)sizeof(T));
+    for (int p = 0; p < PARTS; ++p) {
+      if (p != part) continue;
+      const int i = p * G;
+      unsigned off[G];
+#pragma unroll
+      for (int j = 0; j < G; ++j) off[j] = voff[i + j];
+      if (tile_row0 + ROWS > rows_total) {   // the segment ends inside this tile
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          const int over = tile_row0 + slot_row(wave, i + j, fresh(lane)) - (rows_total - 1);
+          if (over > 0) off[j] -= (unsigned)(over * row_stride * (int64_t)sizeof(T));
+        }
       }
-    }
-#pragma unroll
-    for (int i = 0; i < PER; i += G) {
       const bool second = (wave * PER + i) * 64 >= SLOTS;     // wave-uniform, the same for the whole group
       const char *tb = reinterpret_cast<const char *>((second ? base1 : base0) + (int64_t)tile_row0 * row_stride);
       const unsigned dst = stage + (unsigned)((wave * PER + i) * 1024);
-      issue_group<G>(dst, tb, off[i], off[G > 1 ? i + 1 : i], off[G > 2 ? i + 2 : i], off[G > 2 ? i + 3 : i]);
+      issue_group<G>(dst, tb, off[0], off[G > 1 ? 1 : 0], off[G > 2 ? 2 : 0], off[G > 2 ? 3 : 0]);
     }
   }
 };

@@ -15,12 +15,12 @@ using namespace s1f;
 // K/V tile (BN), rows per staged Q/dO tile (BQ).
 template <typename T> struct Shape;
 //   forward: FNQ query blocks per wave, FKB 32-key blocks per LDS tile, FNW waves, FOCC waves per SIMD
-//   dq:      QNQ, QBN keys per LDS tile, QOCC;   dk/dv: NK key blocks per wave, BQ rows per Q/dO tile, KOCC
+//   dq:      QNQ, QBN keys per LDS tile, QOCC;   dk/dv: KNW waves (32 keys each), copy distance KDIST, phase lag KLAG
 template <> struct Shape<bf16_t> {
-  static constexpr int FNQ = 1, FKB = 2, FNW = 8, FOCC = 2, QNQ = 1, QBN = 64, QOCC = 2, NK = 1, BQ = 32, KOCC = 2;
+  static constexpr int FNQ = 1, FKB = 2, FNW = 8, FOCC = 2, QNQ = 1, QBN = 64, QOCC = 2, KNW = 8, KDIST = 2, KLAG = 1;
 };
 template <> struct Shape<float> {
-  static constexpr int FNQ = 1, FKB = 1, FNW = 4, FOCC = 1, QNQ = 1, QBN = 32, QOCC = 1, NK = 1, BQ = 32, KOCC = 1;
+  static constexpr int FNQ = 1, FKB = 1, FNW = 4, FOCC = 1, QNQ = 1, QBN = 32, QOCC = 1, KNW = 4, KDIST = 1, KLAG = 0;
 };
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -88,10 +88,10 @@ template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, const AttnArgs &
 
 template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
   typedef Shape<T> S;
-  typedef BwdDkdvCfg<T, D, S::NK, S::BQ> KC;
+  typedef BwdDkdvCfg<T, D, S::KNW, S::KDIST, S::KLAG> KC;
   const int kv_len = a.seg_off + a.seg_len;
-  return launch(seg_attn_bwd_dkdv_kernel<T, D, S::NK, S::BQ, S::KOCC>, (kv_len + KC::BNW - 1) / KC::BNW,
-                d->n_kv_heads * d->batch, 256, KC::LDS_BYTES, a, st);
+  return launch(seg_attn_bwd_dkdv_kernel<T, D, S::KNW, S::KDIST, S::KLAG>, (kv_len + KC::BNW - 1) / KC::BNW,
+                d->n_kv_heads * d->batch, KC::THREADS, KC::LDS_BYTES, a, st);
 }
 
 
