@@ -189,11 +189,6 @@ S1F_DEV int fresh(int x) {
   asm volatile("" : "+v"(x));
   return x;
 }
-// The same for a wave-uniform value (stays in a scalar register).
-S1F_DEV unsigned fresh_uniform(unsigned x) {
-  asm volatile("" : "+s"(x));
-  return x;
-}
 
 // Reads operand fragments of 32-row blocks out of an LdsTile.  The swizzle depends on the row modulo 16
 // only, so for a block starting at a multiple of 16 rows every address is (block base: uniform) combined
@@ -306,126 +301,28 @@ template <int ROWS, int D> struct FragReader<LdsTile<float, ROWS, D>, float> {
   }
 };
 
-// Register-staged copy of a [ROWS x D] tile from global memory (row stride in elements) into an
-// LdsTile, by NT threads, 16 bytes per access.  Rows >= rows_valid are filled with zeros.
-template <typename T, int ROWS, int D, int NT> struct TileCopy {
-  typedef LdsTile<T, ROWS, D> TL;
-  static constexpr int TOTAL = ROWS * TL::CPR;
-  static constexpr int PER = (TOTAL + NT - 1) / NT;
-  u32x4 regs[PER];
-
-  S1F_DEV void load(const T *base, int64_t row_stride, int rows_valid, int tid) {
-    if (rows_valid >= ROWS) {   // whole tile in range (the common case): no per-row predicate
-#pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        const int id = tid + i * NT;
-        const int r = id / TL::CPR, c = id % TL::CPR;
-        if (TOTAL % NT == 0 || id < TOTAL)
-          regs[i] = *reinterpret_cast<const u32x4 *>(base + (int64_t)r * row_stride + c * TL::CE);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        const int id = tid + i * NT;
-        const int r = id / TL::CPR, c = id % TL::CPR;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if ((TOTAL % NT == 0 || id < TOTAL) && r < rows_valid)
-          v = *reinterpret_cast<const u32x4 *>(base + (int64_t)r * row_stride + c * TL::CE);
-        regs[i] = v;
-      }
-    }
-  }
-  S1F_DEV void store(char *tile, int tid) const {
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int id = tid + i * NT;
-      const int r = id / TL::CPR, c = id % TL::CPR;
-      if (TOTAL % NT == 0 || id < TOTAL) *reinterpret_cast<u32x4 *>(tile + TL::chunk_off(r, c)) = regs[i];
-    }
-  }
-};
-
-// Asynchronous copy of a K tile and a V tile ([ROWS x D] each, V right behind K in LDS) from global
+// Asynchronous copy of two [ROWS x D] tiles (say a K tile and the V tile right behind it in LDS) from global
 // memory straight into LdsTiles (no register staging) by the NW waves of a workgroup.  One
 // global_load_lds_dwordx4 moves 16 bytes per lane into 1 KiB of consecutive LDS: lane l lands at
 // M0 + immediate offset + 16*l, and the immediate offset is added to the global address as well.  The
 // instruction that fills 16-byte slots [64*n, 64*n+64) of a tile makes lane l fetch the chunk that the
 // swizzle places in slot 64*n + l.  Each wave fills one contiguous range of the pair of tiles, and up to
 // four of its instructions share one value of M0 (told apart by the immediate offset): rewriting M0
-// between copies makes them complete one after the other instead of overlapping.
-// Rows past `rows_total` re-read the last valid row (callers mask them); slots of padding columns
-// (head_dim 80) re-read a valid chunk of the same row.  Completion is tracked by the wave's vmcnt.
-template <typename T, int ROWS, int D, int NW> struct AsyncTilePair {
-  typedef LdsTile<T, ROWS, D> TL;
-  static constexpr int SLOTS = ROWS * TL::RS;           // 16-byte slots per tile
-  static constexpr int PER = 2 * SLOTS / (64 * NW);     // instructions per wave for the pair
-  static_assert((2 * SLOTS) % (64 * NW) == 0 && SLOTS % 64 == 0, "tiles must split evenly over the waves");
-  static_assert(PER <= 4 || PER % 4 == 0, "instructions are issued in groups of up to four");
-  int row[PER];     // tile row fetched by this lane in instruction i
-  int coff[PER];    // element offset of its chunk inside the row
-
-  S1F_DEV void init(int wave, int lane) {
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int slot = ((wave * PER + i) * 64 + lane) % SLOTS;
-      const int r = slot / TL::RS, pos = slot % TL::RS;
-      int c = pos ^ TL::swz(r);
-      if (TL::CPR < TL::RS && c >= TL::CPR) c &= TL::RS / 2 - 1;
-      row[i] = r;
-      coff[i] = c * TL::CE;
-    }
-  }
-
-  template <int N> S1F_DEV static void issue_group(unsigned dst, const T *p0, const T *p1, const T *p2, const T *p3) {
-    // Written as assembly so that the compiler's wait-count pass does not tie later LDS reads of OTHER
-    // ring stages to these copies (it would wait for them before the first LDS read); the callers order
-    // the copies against their readers with wait_async_tiles() + a workgroup barrier.
-    const char *q0 = reinterpret_cast<const char *>(p0), *q1 = reinterpret_cast<const char *>(p1) - 1024,
-               *q2 = reinterpret_cast<const char *>(p2) - 2048, *q3 = reinterpret_cast<const char *>(p3) - 3072;
-    if (N == 1)
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(q0) : "m0");
-    else if (N == 2)
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
-                   "global_load_lds_dwordx4 %2, off offset:1024" : : "s"(dst), "v"(q0), "v"(q1) : "m0");
-    else
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
-                   "global_load_lds_dwordx4 %2, off offset:1024\n\t"
-                   "global_load_lds_dwordx4 %3, off offset:2048\n\t"
-                   "global_load_lds_dwordx4 %4, off offset:3072" : : "s"(dst), "v"(q0), "v"(q1), "v"(q2), "v"(q3) : "m0");
-  }
-
-  // kbase/vbase: row 0 of the head's K and V; tile_row0: first row of the tile; stage: LDS address of the K tile
-  S1F_DEV void issue(const T *kbase, const T *vbase, int64_t row_stride, int tile_row0, int rows_total,
-                     lds_addr stage, int wave) const {
-    const T *p[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      int r = tile_row0 + row[i];
-      r = r < rows_total ? r : rows_total - 1;
-      const bool is_v = (wave * PER + i) * 64 >= SLOTS;     // wave-uniform
-      p[i] = (is_v ? vbase : kbase) + (int64_t)r * row_stride + coff[i];
-    }
-    static_assert(PER == 1 || PER == 2 || PER % 4 == 0, "group shape");
-    constexpr int G = PER < 4 ? PER : 4;
-#pragma unroll
-    for (int i = 0; i < PER; i += G) {
-      const unsigned dst = stage + (unsigned)((wave * PER + i) * 1024);
-      issue_group<G>(dst, p[i], p[G > 1 ? i + 1 : i], p[G > 2 ? i + 2 : i], p[G > 2 ? i + 3 : i]);
-    }
-  }
-};
-
-// The same copy for two tiles whose rows all lie `row_stride` apart from one wave-uniform base each: the
-// address is (scalar base of the tile) + (32-bit lane offset fixed at init), which keeps one register per
-// instruction instead of a row, a column and a 64-bit pointer.  Rows past `rows_total` re-read the last
-// valid row.  (ROWS - 1) * row_stride * sizeof(T) + row bytes must fit 32 bits.
-template <typename T, int ROWS, int D, int NW> struct AsyncTilePairU {
+// between copies makes them complete one after the other instead of overlapping.  They are written as
+// assembly so that the compiler's wait-count pass does not tie later LDS reads of OTHER ring stages to
+// these copies; callers order the copies against their readers with wait_async_tiles() + a workgroup
+// barrier.  Completion is tracked by the wave's vmcnt.
+// The rows of a tile lie `row_stride` apart from one wave-uniform base per tensor: the address is (scalar
+// base of the tile) + (32-bit lane offset fixed at init), one register per instruction.  Rows past
+// `rows_total` re-read the last valid row (callers mask them); slots of padding columns (head_dim 80)
+// re-read a valid chunk of the same row.  (ROWS - 1) * row_stride * sizeof(T) + row bytes must fit 32 bits.
+template <typename T, int ROWS, int D, int NW, int GMAX = 4> struct AsyncTilePairU {
   typedef LdsTile<T, ROWS, D> TL;
   static constexpr int SLOTS = ROWS * TL::RS;
   static constexpr int PER = 2 * SLOTS / (64 * NW);
-  static constexpr int G = PER < 4 ? PER : 4;
+  static constexpr int G = PER < GMAX ? PER : GMAX;    // instructions per group (one value of M0 each)
   static_assert((2 * SLOTS) % (64 * NW) == 0 && SLOTS % (64 * G) == 0, "tiles must split evenly over the waves");
-  static_assert(PER == 1 || PER == 2 || PER % 4 == 0, "instructions are issued in groups of up to four");
+  static_assert(PER % G == 0 && (G == 1 || G == 2 || G == 4), "instructions are issued in groups of one, two or four");
   unsigned voff[PER];   // byte offset of this lane's chunk from the first row of its tile
 
   S1F_DEV static int slot_row(int wave, int i, int lane) { return (((wave * PER + i) * 64 + lane) % SLOTS) / TL::RS; }
@@ -442,7 +339,13 @@ template <typename T, int ROWS, int D, int NW> struct AsyncTilePairU {
   }
 
   template <int N>
-  S1F_DEV static void issue_group(unsigned dst, const char *tb, unsigned o0, unsigned o1, unsigned o2, unsigned o3) {
+  S1F_DEV static void issue_group(unsigned dst_, const char *tb_, unsigned o0, unsigned o1, unsigned o2, unsigned o3) {
+    // both are wave-uniform by construction; say so where the compiler cannot prove it
+    const unsigned dst = __builtin_amdgcn_readfirstlane(dst_);
+    const uint64_t tbits = reinterpret_cast<uint64_t>(tb_);
+    const char *tb = reinterpret_cast<const char *>(
+        ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(tbits >> 32)) << 32) |
+        (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)tbits));
     if (N == 1)
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(dst), "v"(o0), "s"(tb) : "m0");
     else if (N == 2)

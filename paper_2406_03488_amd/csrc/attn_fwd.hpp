@@ -214,10 +214,22 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   const int n_kt = (n_blk + KB - 1) / KB;
 
   const lds_addr lds0 = to_lds_addr(smem);
-  AsyncTilePair<T, BN, D, NW> ld;
-  ld.init(wave, lane);
+  // The wave's share of a tile's copy is issued in KB parts, one per 32-key step, so that the waves of the
+  // workgroup do not queue behind each other's copies right after the barrier.
+  constexpr int PER_STEP = (2 * BN * KT::RS / (64 * NW)) / KB;   // copy instructions per wave and step
+  typedef AsyncTilePairU<T, BN, D, NW, (PER_STEP < 4 ? PER_STEP : 4)> LD;
+  static_assert(LD::PARTS % KB == 0, "the copy splits evenly over the 32-key steps");
+  LD ld;
+  ld.init(wave, lane, a.kv_ss);
+  auto issue_part = [&](int jt, int step_part) {
+#pragma unroll
+    for (int p = 0; p < LD::PARTS / KB; ++p)
+      ld.issue_part(step_part * (LD::PARTS / KB) + p, kbase, vbase, a.kv_ss, jt * BN, kv_len,
+                    lds0 + (jt % 3) * Cfg::STAGE_BYTES, wave, lane);
+  };
   auto issue = [&](int jt) {
-    ld.issue(kbase, vbase, a.kv_ss, jt * BN, kv_len, lds0 + (jt % 3) * Cfg::STAGE_BYTES, wave);
+#pragma unroll
+    for (int p = 0; p < KB; ++p) issue_part(jt, p);
   };
   issue(0);
   if (n_kt > 1) issue(1);
@@ -282,7 +294,11 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
 #endif
         __syncthreads();      // ... and everyone's; every wave has also finished reading tile jt-1
         S1F_TRACE_MARK(6);
-        if (jt + 2 < n_kt) issue(jt + 2);
+      }
+      // tile jt+2 (for kb = KB-1; the later parts follow in the steps of tile jt+1) goes to the stage of tile jt-1
+      {
+        const int part = (kb + 1) % KB, jt_new = kb == KB - 1 ? jt + 2 : jt + 1;
+        if (jt_new >= 2 && jt_new < n_kt) issue_part(jt_new, part);
       }
       S1F_TRACE_MARK(1);
       const lds_addr vblock = lds0 + (jt % 3) * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
