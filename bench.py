@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--workload", default="7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unsegmented", action="store_true")
+    ap.add_argument("--no-balance", action="store_true", help="skip the cwp-vs-uniform load-balance report")
+    ap.add_argument("--no-mfma-probe", action="store_true", help="skip the measured matrix-peak microbenchmark")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 1 GiB device-to-device copy first (reference for HBM byte counters)")
     return ap.parse_args()
@@ -51,6 +53,29 @@ def measured_traffic(kernel, workload):
 def seg_pairs(bounds):
     """Causal (query, key) pairs per head of each segment."""
     return [(b - a) * a + (b - a) * (b - a + 1) // 2 for a, b in zip(bounds[:-1], bounds[1:])]
+
+
+def measured_mfma_peak(torch):
+    """TFLOP/s of register-resident back-to-back v_mfma_f32_32x32x16_bf16 on every SIMD (two waves per SIMD),
+    measured in this run with the probe kernel of libs1f_probe.so."""
+    import ctypes
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2406_03488_amd", "libs1f_probe.so"))
+    lib.s1f_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    lib.s1f_probe_mfma_bf16.restype = ctypes.c_int
+    wgs, iters = 512, 4000
+    sink = torch.zeros(wgs * 256, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    best = 0.0
+    for rep in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        if lib.s1f_probe_mfma_bf16(wgs, iters, sink.data_ptr(), stream) != 0:
+            raise RuntimeError("matrix-peak probe failed to launch")
+        e1.record()
+        torch.cuda.synchronize()
+        flops = wgs * 4 * 16.0 * iters * 32768.0
+        best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
 
 
 class Stage:
@@ -119,11 +144,43 @@ class Stage:
         for _ in range(warmup):
             self.step(**kw)
         torch.cuda.synchronize()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         t0 = time.perf_counter()
-        for _ in range(steps):
+        marks[0].record()
+        for i in range(steps):
             self.step(record=True, **kw)
+            marks[i + 1].record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / steps
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        self.step_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+        return ms
+
+
+def balance_report(stage, w, seg_ms, bounds, kernels, args):
+    """Load balance of the partition (Section 3.4): max/mean over segments of attention time (measured,
+    forward + backward of the segment) plus linear-layer time.  The linear layers are not built here: their
+    time is MODELLED as 3 * 24 * hidden^2 * n_i FLOPs (forward + backward of one layer's matrices) at the
+    TFLOP/s this run achieved on attention.  The uniform partition is measured the same way for comparison."""
+    def ratio(bnds, per_seg_ms):
+        att = [sum(per_seg_ms[k][i] for k in per_seg_ms) for i in range(len(bnds) - 1)]
+        tot_att_flops = 14.0 * w.head_dim * w.n_q_heads * (w.seq_len * (w.seq_len + 1) // 2)
+        rate = tot_att_flops / (sum(att) * 1e-3)                       # FLOP/s achieved on attention
+        lin = [72.0 * w.hidden ** 2 * (b - a) / rate * 1e3 for a, b in zip(bnds[:-1], bnds[1:])]
+        both = [x + y for x, y in zip(att, lin)]
+        return {"attention_only_max_over_mean": max(att) / (sum(att) / len(att)),
+                "with_modelled_linear_max_over_mean": max(both) / (sum(both) / len(both)),
+                "attention_ms": att, "modelled_linear_ms": lin}
+    rep = {"partition": w.partition, "this": ratio(bounds, seg_ms), "linear_term": "modelled, not measured"}
+    if w.partition == "cwp":
+        stage.events = []
+        steps = max(2, args.steps // 3)
+        stage.run(steps, 1, kind="uniform")
+        ub = stage.boundaries(kind="uniform")
+        useg = {}
+        for kind, i, e0, e1 in stage.events:
+            useg.setdefault(kind, [0.0] * (len(ub) - 1))[i] += e0.elapsed_time(e1) / steps
+        rep["uniform"] = ratio(ub, useg)
+    return rep
 
 
 def cpu_baseline(stage, torch):
@@ -218,6 +275,17 @@ def main():
                       ((kernels["bwd_dq"]["ms_per_step"] + kernels["bwd_dkdv"]["ms_per_step"]) * 1e-3) / 1e12,
         "kernels": kernels, "segment_ms": seg_ms, "roofline": roofline,
     }
+    sm = stage.step_ms
+    mean = sum(sm) / len(sm)
+    result["step_ms_mean"] = mean
+    result["step_ms_std"] = (sum((x - mean) ** 2 for x in sm) / max(1, len(sm) - 1)) ** 0.5
+    if not args.no_mfma_probe and w.dtype == "bf16":
+        mp = measured_mfma_peak(torch)
+        result["measured_mfma_peak_tflops"] = mp
+        result["pct_of_measured_peak"] = 100.0 * result["value"] / mp
+        roofline["frac_of_measured_peak"] = roofline["achieved"] / mp
+    if not args.no_balance:
+        result["balance"] = balance_report(stage, w, seg_ms, bounds, kernels, args)
     if not args.no_unsegmented:
         stage.events = []
         ms1 = stage.run(max(2, args.steps // 3), 1, n_seg=1, kind="uniform")

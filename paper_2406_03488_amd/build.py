@@ -8,6 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libs1f.so")
+PROBE_LIB = os.path.join(HERE, "libs1f_probe.so")   # measurement aid used by bench.py only
 
 SOURCES = ["s1f_api.hip", "s1f_partition.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
@@ -23,6 +24,10 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
     if verbose:
         print(proc.stderr)
+    cmd = [hipcc, *FLAGS, "-o", PROBE_LIB, os.path.join(CSRC, "mfma_peak.hip")]
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
     return LIB
 
 
