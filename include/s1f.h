@@ -123,6 +123,30 @@ int s1f_seg_attn_bwd_dkdv(const s1f_desc *desc, const void *dout, const void *q_
 /* Bytes of device scratch s1f_seg_attn_bwd needs for this call shape (0 on invalid arguments). */
 size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len);
 
+/* Order of passes of one pipeline device under the sequence-level 1F1B schedule (Section 3.2).  HOST
+ * functions, no device work.
+ *
+ * pp_size = P devices, device = i in [1, P], n_micro = M micro-batches, n_seg = k segments per sequence.
+ * s1f_seq1f1b_warmup writes the number of sub-sequences the device forwards before its first backward
+ * pass, Eq. 4: P - i - 1 + k if M > P; otherwise every forward pass comes first (M * k sub-sequences: the
+ * equation prints M, the micro-batch count of Eq. 1).  Never more than M * k.
+ * s1f_seq1f1b_order writes the 2 * M * k passes in execution order into the caller-owned HOST array `order`
+ * (capacity in elements) and their number into *n_passes (also when `order` is NULL or too small, which
+ * returns S1F_EINVAL, so that a caller can size the array): the warm-up forward passes; then one forward
+ * pass followed by one backward pass per step; then the remaining backward passes.  A backward pass takes
+ * the tail segment of the earliest micro-batch that still has one (first-in-first-out over micro-batches,
+ * last-in-first-out over the segments of a micro-batch), so for every micro-batch the calls of
+ * s1f_seg_attn_fwd run for segments 0 .. k-1 and those of s1f_seg_attn_bwd for k-1 .. 0.
+ * Errors: S1F_EINVAL for P < 1, i outside [1, P], M < 1, k < 1, M * k > 2^40 or a NULL result pointer. */
+typedef struct {
+  int32_t micro_batch; /* 0-based */
+  int32_t segment;     /* 0-based */
+  int32_t backward;    /* 0 = forward pass, 1 = backward pass */
+} s1f_pass;
+int s1f_seq1f1b_warmup(int32_t pp_size, int32_t device, int32_t n_micro, int32_t n_seg, int64_t *warmup);
+int s1f_seq1f1b_order(int32_t pp_size, int32_t device, int32_t n_micro, int32_t n_seg, s1f_pass *order,
+                      int64_t capacity, int64_t *n_passes);
+
 /* Static, NUL-terminated description of a status code. */
 const char *s1f_strerror(int status);
 

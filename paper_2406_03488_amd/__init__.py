@@ -6,7 +6,9 @@ memory and the current stream.  There is no fallback: if the shared library is m
 compute entry points raises.
 """
 from .binding import (Desc, S1FError, bwd_workspace_bytes, library_path, load_library, partition,
-                      seg_attn_bwd, seg_attn_bwd_dkdv, seg_attn_bwd_dq, seg_attn_fwd, strerror, version)
+                      seg_attn_bwd, seg_attn_bwd_dkdv, seg_attn_bwd_dq, seg_attn_fwd, seq1f1b_order,
+                      seq1f1b_warmup, strerror, version)
 
 __all__ = ["Desc", "S1FError", "bwd_workspace_bytes", "library_path", "load_library", "partition",
-           "seg_attn_bwd", "seg_attn_bwd_dkdv", "seg_attn_bwd_dq", "seg_attn_fwd", "strerror", "version"]
+           "seg_attn_bwd", "seg_attn_bwd_dkdv", "seg_attn_bwd_dq", "seg_attn_fwd", "seq1f1b_order", "seq1f1b_warmup",
+           "strerror", "version"]

@@ -26,6 +26,10 @@ class Desc(ctypes.Structure):
                 ("kv_capacity", ctypes.c_int64)]
 
 
+class Pass(ctypes.Structure):
+    _fields_ = [("micro_batch", ctypes.c_int32), ("segment", ctypes.c_int32), ("backward", ctypes.c_int32)]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -53,6 +57,10 @@ def load_library():
     lib.s1f_seg_attn_bwd_dkdv.restype = ctypes.c_int
     lib.s1f_bwd_workspace_bytes.argtypes = [dp, i64, i64]
     lib.s1f_bwd_workspace_bytes.restype = sz
+    lib.s1f_seq1f1b_warmup.argtypes = [i32, i32, i32, i32, ctypes.POINTER(i64)]
+    lib.s1f_seq1f1b_warmup.restype = ctypes.c_int
+    lib.s1f_seq1f1b_order.argtypes = [i32, i32, i32, i32, ctypes.POINTER(Pass), i64, ctypes.POINTER(i64)]
+    lib.s1f_seq1f1b_order.restype = ctypes.c_int
     lib.s1f_strerror.argtypes = [ctypes.c_int]
     lib.s1f_strerror.restype = ctypes.c_char_p
     lib.s1f_version.argtypes = []
@@ -77,6 +85,27 @@ def partition(seq_len: int, n_seg: int, hidden: int, heads: int):
     if rc != 0:
         raise S1FError(rc, "s1f_partition")
     return list(out)
+
+
+def seq1f1b_warmup(pp_size: int, device: int, n_micro: int, n_seg: int) -> int:
+    """s1f_seq1f1b_warmup: sub-sequences forwarded before the first backward pass."""
+    w = ctypes.c_int64(0)
+    rc = load_library().s1f_seq1f1b_warmup(int(pp_size), int(device), int(n_micro), int(n_seg), ctypes.byref(w))
+    if rc != 0:
+        raise S1FError(rc, "s1f_seq1f1b_warmup")
+    return int(w.value)
+
+
+def seq1f1b_order(pp_size: int, device: int, n_micro: int, n_seg: int):
+    """s1f_seq1f1b_order: list of ("F" | "B", micro_batch, segment) in execution order."""
+    lib = load_library()
+    n = ctypes.c_int64(0)
+    cap = 2 * max(int(n_micro), 0) * max(int(n_seg), 0)
+    buf = (Pass * max(cap, 1))()
+    rc = lib.s1f_seq1f1b_order(int(pp_size), int(device), int(n_micro), int(n_seg), buf, cap, ctypes.byref(n))
+    if rc != 0:
+        raise S1FError(rc, "s1f_seq1f1b_order")
+    return [("B" if buf[i].backward else "F", int(buf[i].micro_batch), int(buf[i].segment)) for i in range(n.value)]
 
 
 def _dtype_code(t):

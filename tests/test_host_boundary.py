@@ -89,3 +89,29 @@ def test_attention_entry_points_validate_before_any_launch():
     assert lib.s1f_bwd_workspace_bytes(ctypes.byref(_desc()), 500, 256) == 0
     for code in range(0, 6):
         assert isinstance(s1f.strerror(code), str) and s1f.strerror(code)
+
+
+def test_seq1f1b_order_matches_oracle():
+    """The library enumerates the order in closed form; the oracle simulates the queue of Section 3.2."""
+    from oracle import schedule as SCH
+    for P_ in (1, 2, 3, 4, 8):
+        for i in range(1, P_ + 1):
+            for M in (1, 2, 3, 4, 7, 9, 16, 33):
+                for k in (1, 2, 3, 4, 8):
+                    assert s1f.seq1f1b_warmup(P_, i, M, k) == SCH.warmup_count(P_, i, M, k), (P_, i, M, k)
+                    assert s1f.seq1f1b_order(P_, i, M, k) == SCH.stage_order(P_, i, M, k), (P_, i, M, k)
+
+
+def test_seq1f1b_rejects_bad_arguments():
+    for bad in ((0, 1, 4, 2), (4, 0, 4, 2), (4, 5, 4, 2), (4, 1, 0, 2), (4, 1, 4, 0)):
+        with pytest.raises(s1f.S1FError) as e:
+            s1f.seq1f1b_order(*bad)
+        assert e.value.status == 1
+        with pytest.raises(s1f.S1FError):
+            s1f.seq1f1b_warmup(*bad)
+    lib = s1f.load_library()
+    n = ctypes.c_int64(0)
+    buf = (binding.Pass * 4)()
+    assert lib.s1f_seq1f1b_order(2, 1, 3, 2, buf, 4, ctypes.byref(n)) == 1      # too small: size reported
+    assert n.value == 12
+    assert lib.s1f_seq1f1b_order(2, 1, 3, 2, None, 0, ctypes.byref(n)) == 1 and n.value == 12
