@@ -156,6 +156,31 @@ class Stage:
         return ms
 
 
+def cache_kernels_report(stage, w, torch, s1f, bounds):
+    """The data movements around the attention calls (K/V append before each forward, final dK/dV rows emitted
+    after each backward), timed outside the step: HBM-bound, reported against the 8 TB/s peak."""
+    e = 2 if w.dtype == "bf16" else 4
+    kc, vc = torch.empty_like(stage.k), torch.empty_like(stage.v)
+    dko, dvo = torch.empty_like(stage.k), torch.empty_like(stage.v)
+    segs = list(zip(bounds[:-1], bounds[1:]))
+
+    def timed(fn, reps=5):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    t_app = timed(lambda: [s1f.kv_append(stage.k[:, :, a:b], stage.v[:, :, a:b], a, kc, vc) for a, b in segs])
+    t_emit = timed(lambda: [s1f.kv_grad_emit(stage.dk, stage.dv, a, dko[:, :, a:b], dvo[:, :, a:b]) for a, b in segs])
+    elems = 2.0 * w.seq_len * w.n_kv_heads * w.head_dim          # K and V
+    return {"kv_append": {"ms_per_sequence": t_app, "GB_per_s": elems * 2 * e / (t_app * 1e-3) / 1e9},
+            "kv_grad_emit": {"ms_per_sequence": t_emit, "GB_per_s": elems * (4 + e) / (t_emit * 1e-3) / 1e9},
+            "bound": "hbm", "peak_GB_per_s": 8000.0, "launches_per_sequence": len(segs)}
+
+
 def balance_report(stage, w, seg_ms, bounds, kernels, args):
     """Load balance of the partition (Section 3.4): max/mean over segments of attention time (measured,
     forward + backward of the segment) plus linear-layer time.  The linear layers are not built here: their
@@ -284,6 +309,7 @@ def main():
         result["measured_mfma_peak_tflops"] = mp
         result["pct_of_measured_peak"] = 100.0 * result["value"] / mp
         roofline["frac_of_measured_peak"] = roofline["achieved"] / mp
+    result["cache_kernels"] = cache_kernels_report(stage, w, torch, s1f, bounds)
     if not args.no_balance:
         result["balance"] = balance_report(stage, w, seg_ms, bounds, kernels, args)
     if not args.no_unsegmented:

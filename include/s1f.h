@@ -123,6 +123,27 @@ int s1f_seg_attn_bwd_dkdv(const s1f_desc *desc, const void *dout, const void *q_
 /* Bytes of device scratch s1f_seg_attn_bwd needs for this call shape (0 on invalid arguments). */
 size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len);
 
+/* The two data movements on either side of a segment's attention calls (Section 3.2: the keys and values of
+ * all preceding tokens are retained; gradients of earlier tokens are accumulated until the backward passes
+ * of all later segments have run).
+ *
+ * s1f_kv_append copies the segment's new rows k_seg, v_seg [batch, n_kv_heads, seg_len, head_dim] (strides
+ * seg_stride_* in elements, head_dim contiguous) into rows [seg_off, seg_off + seg_len) of the caches k_cache,
+ * v_cache (kv_* strides of desc), before s1f_seg_attn_fwd of that segment.
+ * s1f_kv_grad_emit reads rows [seg_off, seg_off + seg_len) of the fp32 accumulators dk_prefix_acc,
+ * dv_prefix_acc (kv_* strides) after s1f_seg_attn_bwd of that segment, when they are final, and writes them in
+ * desc->dtype (bf16: round to nearest even) to dk_seg, dv_seg [batch, n_kv_heads, seg_len, head_dim]
+ * (seg_stride_*).  n_q_heads, q_stride_* of desc are not used.
+ * All pointers are device pointers, 16-byte aligned; all strides multiples of 8 elements; head_dim a multiple
+ * of 8.  Errors: S1F_EINVAL (null/misaligned pointer, bad stride), S1F_EUNSUPPORTED (dtype, head_dim),
+ * S1F_ERANGE (rows outside [0, kv_capacity)), S1F_EDEVICE. */
+int s1f_kv_append(const s1f_desc *desc, const void *k_seg, const void *v_seg, int64_t seg_stride_b,
+                  int64_t seg_stride_h, int64_t seg_stride_s, int64_t seg_off, int64_t seg_len, void *k_cache,
+                  void *v_cache, void *hip_stream);
+int s1f_kv_grad_emit(const s1f_desc *desc, const float *dk_prefix_acc, const float *dv_prefix_acc, int64_t seg_off,
+                     int64_t seg_len, void *dk_seg, void *dv_seg, int64_t seg_stride_b, int64_t seg_stride_h,
+                     int64_t seg_stride_s, void *hip_stream);
+
 /* Order of passes of one pipeline device under the sequence-level 1F1B schedule (Section 3.2).  HOST
  * functions, no device work.
  *

@@ -57,6 +57,10 @@ def load_library():
     lib.s1f_seg_attn_bwd_dkdv.restype = ctypes.c_int
     lib.s1f_bwd_workspace_bytes.argtypes = [dp, i64, i64]
     lib.s1f_bwd_workspace_bytes.restype = sz
+    lib.s1f_kv_append.argtypes = [dp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp]
+    lib.s1f_kv_append.restype = ctypes.c_int
+    lib.s1f_kv_grad_emit.argtypes = [dp, vp, vp, i64, i64, vp, vp, i64, i64, i64, vp]
+    lib.s1f_kv_grad_emit.restype = ctypes.c_int
     lib.s1f_seq1f1b_warmup.argtypes = [i32, i32, i32, i32, ctypes.POINTER(i64)]
     lib.s1f_seq1f1b_warmup.restype = ctypes.c_int
     lib.s1f_seq1f1b_order.argtypes = [i32, i32, i32, i32, ctypes.POINTER(Pass), i64, ctypes.POINTER(i64)]
@@ -217,3 +221,46 @@ def seg_attn_bwd_dkdv(dout, q_seg, k_prefix, v_prefix, lse, seg_off: int, dk_pre
                                    workspace.numel() * workspace.element_size(), _stream_ptr())
     if rc != 0:
         raise S1FError(rc, "s1f_seg_attn_bwd_dkdv")
+
+
+def _kv_desc(cache) -> Desc:
+    """Descriptor for the cache-side calls: only the kv_* fields, dtype, batch and head_dim are read."""
+    if cache.dim() != 4 or cache.stride(3) != 1:
+        raise ValueError("expected a [batch, kv_heads, capacity, head_dim] tensor with contiguous head_dim")
+    b, h, cap, d = cache.shape
+    return Desc(batch=b, n_q_heads=h, n_kv_heads=h, head_dim=d, dtype=0, reserved=0, q_stride_b=0, q_stride_h=0,
+                q_stride_s=d, kv_stride_b=cache.stride(0), kv_stride_h=cache.stride(1), kv_stride_s=cache.stride(2),
+                kv_capacity=cap)
+
+
+def kv_append(k_seg, v_seg, seg_off: int, k_cache, v_cache):
+    """s1f_kv_append: rows of the segment -> rows [seg_off, seg_off + seg_len) of the caches."""
+    lib = load_library()
+    _same_layout(k_seg, v_seg)
+    _same_layout(k_cache, v_cache)
+    desc = _kv_desc(k_cache)
+    desc.dtype = _dtype_code(k_cache)
+    if k_seg.dtype != k_cache.dtype or k_seg.stride(3) != 1:
+        raise ValueError("segment and cache must share the element type; head_dim must be contiguous")
+    rc = lib.s1f_kv_append(ctypes.byref(desc), k_seg.data_ptr(), v_seg.data_ptr(), k_seg.stride(0), k_seg.stride(1),
+                           k_seg.stride(2), int(seg_off), k_seg.shape[2], k_cache.data_ptr(), v_cache.data_ptr(),
+                           _stream_ptr())
+    if rc != 0:
+        raise S1FError(rc, "s1f_kv_append")
+
+
+def kv_grad_emit(dk_prefix_acc, dv_prefix_acc, seg_off: int, dk_seg, dv_seg):
+    """s1f_kv_grad_emit: final rows [seg_off, seg_off + seg_len) of the fp32 accumulators -> dk_seg, dv_seg."""
+    import torch
+    lib = load_library()
+    _same_layout(dk_prefix_acc, dv_prefix_acc)
+    _same_layout(dk_seg, dv_seg)
+    if dk_prefix_acc.dtype != torch.float32 or dk_seg.stride(3) != 1:
+        raise ValueError("accumulators must be fp32; head_dim must be contiguous")
+    desc = _kv_desc(dk_prefix_acc)
+    desc.dtype = _dtype_code(dk_seg)
+    rc = lib.s1f_kv_grad_emit(ctypes.byref(desc), dk_prefix_acc.data_ptr(), dv_prefix_acc.data_ptr(), int(seg_off),
+                              dk_seg.shape[2], dk_seg.data_ptr(), dv_seg.data_ptr(), dk_seg.stride(0), dk_seg.stride(1),
+                              dk_seg.stride(2), _stream_ptr())
+    if rc != 0:
+        raise S1FError(rc, "s1f_kv_grad_emit")
