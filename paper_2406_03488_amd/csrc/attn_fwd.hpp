@@ -43,7 +43,7 @@ template <typename T, int D, int NQ, int KB, int NW> struct FwdCfg {
 
 // Number of operand fragments a wave keeps in flight ahead of the matrix instruction that consumes them
 // (LDS latency is three to four 32x32x16 MFMAs).
-constexpr int kPrefetch = 3;
+constexpr int kPrefetch = 2;
 
 // S^T blocks of one 32-key block: s[nq] = K[block rows, :] Q^T   (prologue only; the loop uses fwd_step)
 template <typename RD, typename T, int NQ, int NKS>
@@ -88,11 +88,12 @@ template <int NQ> S1F_DEV void fwd_row_max(const f32x16 (&s)[NQ], float (&mx)[NQ
 // Operand fragments are read from LDS kPrefetch matrix instructions ahead of their use (the V fragments
 // of phase 2 start arriving during the last slots of phase 1); the scheduling fences keep that order in
 // the generated code.  On return mx holds the row maxima of block k+1 in log2 units.
+//   mask_next: block k+1 crosses the diagonal of the wave's rows
 //   lim0_next = (absolute row of this lane's query in query block 0) - (first key of block k+1) - 4g
-template <typename RD, typename T, bool HAS_NEXT, bool MASK_NEXT, int NQ, int NKS, int DB>
+template <typename RD, typename T, bool HAS_NEXT, int NQ, int NKS, int DB>
 S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], const float (&m)[NQ], float (&l)[NQ],
                       float (&mx)[NQ], const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd,
-                      lds_addr kblock_next, lds_addr vblock, float c, int lim0_next
+                      lds_addr kblock_next, lds_addr vblock, float c, bool mask_next, int lim0_next
 #ifdef S1F_TRACE
                       , bool trace_on, unsigned long long (&trace_t)[8]
 #endif
@@ -151,6 +152,16 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) l[nq] += rs[nq];
   S1F_TRACE_MARK(2);
+  // Blocks that cross the diagonal of this wave's rows get their mask here, in a branch of its own that holds
+  // no matrix instruction: two instances of the whole step (with and without mask code) in one loop body make
+  // the compiler keep the output accumulators in two places and copy all 64 registers on every step.
+  if (HAS_NEXT && mask_next) {
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (8 * (v >> 2) + (v & 3) > lim0_next + 32 * nq) sn[nq][v] = -INFINITY;
+  }
 
   float mxv[NQ];
 #pragma unroll
@@ -170,10 +181,7 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
 #pragma unroll
         for (int v = 16 * i / NV; v < 16 * (i + 1) / NV; ++v)
 #pragma unroll
-          for (int nq = 0; nq < NQ; ++nq) {
-            if (MASK_NEXT && 8 * (v >> 2) + (v & 3) > lim0_next + 32 * nq) sn[nq][v] = -INFINITY;
-            mxv[nq] = fmaxf(mxv[nq], sn[nq][v]);
-          }
+          for (int nq = 0; nq < NQ; ++nq) mxv[nq] = fmaxf(mxv[nq], sn[nq][v]);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -306,10 +314,8 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
       const lds_addr kblock_next = lds0 + ((kn / KB) % 3) * Cfg::STAGE_BYTES + (kn % KB) * BLOCK_BYTES;
       const int lim0n = seg_off + wrow0 + ln - 32 * kn - 4 * g;
       // the last block always crosses the diagonal; earlier ones do if their last key is past the wave's first row
-      if (kn + 1 == n_blk || 32 * kn + 31 > seg_off + wrow0)
-        fwd_step<RD, T, true, true>(s, sn, o, m, l, mx, qf, rd, kblock_next, vblock, c, lim0n S1F_TRACE_ARGS);
-      else
-        fwd_step<RD, T, true, false>(s, sn, o, m, l, mx, qf, rd, kblock_next, vblock, c, lim0n S1F_TRACE_ARGS);
+      const bool mask_next = kn + 1 == n_blk || 32 * kn + 31 > seg_off + wrow0;
+      fwd_step<RD, T, true>(s, sn, o, m, l, mx, qf, rd, kblock_next, vblock, c, mask_next, lim0n S1F_TRACE_ARGS);
       S1F_TRACE_MARK(4);
 #ifdef S1F_TRACE
       if (trace_on && k >= 300 && k < 364) {
@@ -340,7 +346,7 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   {   // last block: no next scores to compute
     const int jt = k / KB, kb = k % KB;
     const lds_addr vblock = lds0 + (jt % 3) * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
-    fwd_step<RD, T, false, false>(s, sn, o, m, l, mx, qf, rd, vblock, vblock, c, 0 S1F_TRACE_ARGS);
+    fwd_step<RD, T, false>(s, sn, o, m, l, mx, qf, rd, vblock, vblock, c, false, 0 S1F_TRACE_ARGS);
   }
 
   T *ob = reinterpret_cast<T *>(a.out_w) + b * a.q_sb + h * a.q_sh;

@@ -17,7 +17,7 @@ template <typename T> struct Shape;
 //   forward: FNQ query blocks per wave, FKB 32-key blocks per LDS tile, FNW waves, FOCC waves per SIMD
 //   dq:      QNQ, QBN keys per LDS tile, QOCC;   dk/dv: KNW waves (32 keys each), copy distance KDIST, phase lag KLAG
 template <> struct Shape<bf16_t> {
-  static constexpr int FNQ = 1, FKB = 2, FNW = 8, FOCC = 2, QNQ = 1, QBN = 64, QOCC = 2, KNW = 8, KDIST = 2, KLAG = 1;
+  static constexpr int FNQ = 1, FKB = 1, FNW = 4, FOCC = 3, QNQ = 1, QBN = 64, QOCC = 2, KNW = 8, KDIST = 2, KLAG = 1;
 };
 template <> struct Shape<float> {
   static constexpr int FNQ = 1, FKB = 1, FNW = 4, FOCC = 1, QNQ = 1, QBN = 32, QOCC = 1, KNW = 4, KDIST = 1, KLAG = 0;
