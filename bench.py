@@ -105,8 +105,15 @@ class Stage:
         w = self.w
         n_seg = w.n_seg if n_seg is None else n_seg
         kind = w.partition if kind is None else kind
+        if isinstance(kind, (list, tuple)):           # explicit boundaries
+            return list(kind)
         if kind == "cwp":
             return self.s1f.partition(w.seq_len, n_seg, w.hidden, w.n_q_heads)
+        if kind == "cwp_literal":                      # Eq. 8's per-segment line as printed
+            return self.s1f.partition_ex(w.seq_len, n_seg, w.hidden, w.n_q_heads, self.s1f.COST_LITERAL, 1)
+        if kind.startswith("cwp_aligned"):             # boundaries on multiples of e.g. 128 tokens
+            return self.s1f.partition_ex(w.seq_len, n_seg, w.hidden, w.n_q_heads, self.s1f.COST_ADDITIVE,
+                                         int(kind[len("cwp_aligned"):]))
         return [(i * w.seq_len) // n_seg for i in range(n_seg + 1)]
 
     def step(self, n_seg=None, kind=None, record=False):
@@ -194,17 +201,31 @@ def balance_report(stage, w, seg_ms, bounds, kernels, args):
         both = [x + y for x, y in zip(att, lin)]
         return {"attention_only_max_over_mean": max(att) / (sum(att) / len(att)),
                 "with_modelled_linear_max_over_mean": max(both) / (sum(both) / len(both)),
-                "attention_ms": att, "modelled_linear_ms": lin}
+                "attention_total_ms": sum(att), "attention_ms": att, "modelled_linear_ms": lin}
     rep = {"partition": w.partition, "this": ratio(bounds, seg_ms), "linear_term": "modelled, not measured"}
-    if w.partition == "cwp":
+    if w.partition != "cwp":
+        return rep
+    steps = max(2, args.steps // 3)
+
+    def measure(kind):
         stage.events = []
-        steps = max(2, args.steps // 3)
-        stage.run(steps, 1, kind="uniform")
-        ub = stage.boundaries(kind="uniform")
-        useg = {}
-        for kind, i, e0, e1 in stage.events:
-            useg.setdefault(kind, [0.0] * (len(ub) - 1))[i] += e0.elapsed_time(e1) / steps
-        rep["uniform"] = ratio(ub, useg)
+        stage.run(steps, 1, kind=kind)
+        b = stage.boundaries(kind=kind)
+        seg = {}
+        for knd, i, e0, e1 in stage.events:
+            seg.setdefault(knd, [0.0] * (len(b) - 1))[i] += e0.elapsed_time(e1) / steps
+        r = ratio(b, seg)
+        r["boundaries"] = b
+        return r
+    rep["uniform"] = measure("uniform")
+    rep["cwp_literal"] = measure("cwp_literal")
+    rep["cwp_aligned128"] = measure("cwp_aligned128")
+    # boundaries re-balanced twice on the measured time of each segment (attention measured + linear modelled)
+    cur = dict(rep["this"], boundaries=list(bounds))
+    for _ in range(2):
+        cost_ns = [int(1e6 * (x + y)) for x, y in zip(cur["attention_ms"], cur["modelled_linear_ms"])]
+        cur = measure(stage.s1f.partition_rebalance(cur["boundaries"], cost_ns, 1))
+    rep["cwp_rebalanced_on_measured_time"] = cur
     return rep
 
 

@@ -74,6 +74,39 @@ typedef struct {
  * boundaries == NULL, or sizes whose cost would overflow 2^62. */
 int s1f_partition(int64_t seq_len, int32_t n_seg, int32_t hidden, int32_t heads, int64_t *boundaries);
 
+/* Variants of the partition (Section 3.4, Eq. 7-8).  HOST functions.
+ *
+ * cost_model S1F_COST_ADDITIVE is s1f_partition's rule.  S1F_COST_LITERAL takes the per-segment line of
+ * Eq. 8 as printed: segment (a, b] costs (b - a) * (12*hidden + b) (units of 2*L*hidden FLOPs, its keys counted
+ * up to and including the segment itself for every row).  That cost is not additive over tokens, so the k costs
+ * cannot be made equal; the result is the composition whose largest cost is smallest, and among those the
+ * lexicographically smallest boundaries.
+ * `align` >= 1 restricts b[1] .. b[n_seg-1] to multiples of `align` (the paper does not align; 1 reproduces
+ * s1f_partition).  Additive model: b[i] is the multiple of align in [0, seq_len] nearest in prefix cost to
+ * i/n_seg of the total (smaller on a tie), clamped so that consecutive boundaries differ by at least `align`
+ * and the last segment keeps a token.
+ * Errors: as s1f_partition, plus S1F_EINVAL for align < 1, an unknown cost_model, or fewer than n_seg - 1
+ * multiples of align in [align, seq_len - 1]. */
+typedef enum { S1F_COST_ADDITIVE = 0, S1F_COST_LITERAL = 1 } s1f_cost_model;
+int s1f_partition_ex(int64_t seq_len, int32_t n_seg, int32_t hidden, int32_t heads, int32_t cost_model,
+                     int64_t align, int64_t *boundaries);
+
+/* Re-balances a partition on MEASURED segment costs (Section 3.4's goal, equal time per segment, applied to
+ * what a run actually took instead of the FLOP model of Eq. 8).  HOST function.
+ *
+ *   boundaries_in  [n_seg + 1]  current boundaries, 0 = b[0] < ... < b[n_seg] = sequence length
+ *   seg_cost       [n_seg]      measured cost of each segment in any integer unit (e.g. nanoseconds), >= 0,
+ *                               sum in [1, 2^48]
+ *   boundaries_out [n_seg + 1]  caller-owned; may not alias boundaries_in
+ * Every token of segment i is taken to cost seg_cost[i] / length_i; boundary j becomes the multiple of `align`
+ * whose measured prefix cost is nearest to j/n_seg of the total (smaller on a tie, exact rational comparison),
+ * clamped as in s1f_partition_ex.  Applying it again to the costs measured on its output converges on equal
+ * measured time when the cost per token varies smoothly.
+ * Errors: S1F_EINVAL for null pointers, n_seg < 1 or > 65536, boundaries not strictly increasing from 0,
+ * a negative cost, a zero or too large sum, more than 2^30 tokens, align < 1 or too coarse for n_seg. */
+int s1f_partition_rebalance(int32_t n_seg, const int64_t *boundaries_in, const int64_t *seg_cost, int64_t align,
+                            int64_t *boundaries_out);
+
 /* Forward of one segment (Section 3.1 Eq. 3 restricted to the segment's rows; Section 3.2).
  *
  *   q_seg     [batch, n_q_heads, seg_len, head_dim]  queries of absolute rows seg_off .. seg_off+seg_len-1

@@ -5,10 +5,11 @@ Argument marshalling only: every step runs in the library's HIP kernels.  PyTorc
 memory and the current stream.  There is no fallback: if the shared library is missing, importing the
 compute entry points raises.
 """
-from .binding import (Desc, S1FError, bwd_workspace_bytes, kv_append, kv_grad_emit, library_path, load_library, partition,
-                      seg_attn_bwd, seg_attn_bwd_dkdv, seg_attn_bwd_dq, seg_attn_fwd, seq1f1b_order,
+from .binding import (COST_ADDITIVE, COST_LITERAL, Desc, S1FError, bwd_workspace_bytes, kv_append, kv_grad_emit,
+                      library_path, load_library, partition, partition_ex, partition_rebalance, seg_attn_bwd, seg_attn_bwd_dkdv, seg_attn_bwd_dq, seg_attn_fwd, seq1f1b_order,
                       seq1f1b_warmup, strerror, version)
 
-__all__ = ["Desc", "S1FError", "bwd_workspace_bytes", "kv_append", "kv_grad_emit", "library_path", "load_library", "partition",
+__all__ = ["COST_ADDITIVE", "COST_LITERAL", "Desc", "S1FError", "bwd_workspace_bytes", "kv_append", "kv_grad_emit",
+           "library_path", "load_library", "partition", "partition_ex", "partition_rebalance",
            "seg_attn_bwd", "seg_attn_bwd_dkdv", "seg_attn_bwd_dq", "seg_attn_fwd", "seq1f1b_order", "seq1f1b_warmup",
            "strerror", "version"]

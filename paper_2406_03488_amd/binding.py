@@ -47,6 +47,10 @@ def load_library():
     dp = ctypes.POINTER(Desc)
     lib.s1f_partition.argtypes = [i64, i32, i32, i32, ctypes.POINTER(i64)]
     lib.s1f_partition.restype = ctypes.c_int
+    lib.s1f_partition_ex.argtypes = [i64, i32, i32, i32, i32, i64, ctypes.POINTER(i64)]
+    lib.s1f_partition_ex.restype = ctypes.c_int
+    lib.s1f_partition_rebalance.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i64), i64, ctypes.POINTER(i64)]
+    lib.s1f_partition_rebalance.restype = ctypes.c_int
     lib.s1f_seg_attn_fwd.argtypes = [dp, vp, vp, vp, i64, i64, vp, vp, vp]
     lib.s1f_seg_attn_fwd.restype = ctypes.c_int
     lib.s1f_seg_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
@@ -88,6 +92,33 @@ def partition(seq_len: int, n_seg: int, hidden: int, heads: int):
     rc = lib.s1f_partition(int(seq_len), int(n_seg), int(hidden), int(heads), out)
     if rc != 0:
         raise S1FError(rc, "s1f_partition")
+    return list(out)
+
+
+COST_ADDITIVE, COST_LITERAL = 0, 1
+
+
+def partition_ex(seq_len: int, n_seg: int, hidden: int, heads: int, cost_model: int = COST_ADDITIVE, align: int = 1):
+    """s1f_partition_ex: list of n_seg + 1 boundaries under the chosen cost model and alignment."""
+    out = (ctypes.c_int64 * (max(int(n_seg), 0) + 1))()
+    rc = load_library().s1f_partition_ex(int(seq_len), int(n_seg), int(hidden), int(heads), int(cost_model),
+                                         int(align), out)
+    if rc != 0:
+        raise S1FError(rc, "s1f_partition_ex")
+    return list(out)
+
+
+def partition_rebalance(boundaries, seg_cost, align: int = 1):
+    """s1f_partition_rebalance: new boundaries from the measured integer cost of each segment."""
+    k = len(boundaries) - 1
+    if k < 1 or len(seg_cost) != k:
+        raise S1FError(1, "s1f_partition_rebalance")
+    b_in = (ctypes.c_int64 * (k + 1))(*[int(x) for x in boundaries])
+    cost = (ctypes.c_int64 * k)(*[int(x) for x in seg_cost])
+    out = (ctypes.c_int64 * (k + 1))()
+    rc = load_library().s1f_partition_rebalance(k, b_in, cost, int(align), out)
+    if rc != 0:
+        raise S1FError(rc, "s1f_partition_rebalance")
     return list(out)
 
 

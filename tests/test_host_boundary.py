@@ -48,6 +48,108 @@ def test_partition_rejects_bad_arguments():
     assert lib.s1f_partition(8, 2, 4, 1, None) == 1
 
 
+def test_partition_ex_additive_matches_oracle():
+    for n, k, hidden, align in ((8, 2, 1, 2), (8, 2, 1, 3), (64, 4, 1, 4), (100, 3, 2, 8), (257, 5, 4, 16), (50, 2, 1, 7),
+                                (4096, 8, 512, 128), (32768, 8, 4096, 128), (32768, 8, 4096, 256), (8192, 4, 2560, 64),
+                                (1000, 7, 64, 1), (129, 2, 8, 128), (300, 3, 1, 100)):
+        assert s1f.partition_ex(n, k, hidden, 1, s1f.COST_ADDITIVE, align) == P.partition(n, k, hidden, 1, align)
+    for n in range(1, 30):
+        for k in range(1, 5):
+            for align in (1, 2, 3, 5):
+                if (n - 1) // align < k - 1 or n < k:
+                    continue
+                assert s1f.partition_ex(n, k, 3, 1, 0, align) == P.partition(n, k, 3, 1, align), (n, k, align)
+    assert s1f.partition_ex(32768, 8, 4096, 32) == s1f.partition(32768, 8, 4096, 32)
+
+
+def test_partition_ex_literal_matches_oracle():
+    for n, k, hidden, align in ((8, 2, 1, 1), (6, 3, 1, 1), (8, 2, 1, 4), (100, 4, 8, 1), (300, 7, 16, 1), (257, 5, 4, 16),
+                                (400, 8, 64, 8), (64, 64, 2, 1), (90, 3, 1000, 1), (350, 6, 1, 1), (385, 4, 12, 128)):
+        assert s1f.partition_ex(n, k, hidden, 1, s1f.COST_LITERAL, align) == P.partition_literal(n, k, hidden, 1, align)
+    for n in range(1, 26):
+        for k in range(1, 5):
+            for align in (1, 2, 4):
+                if (n - 1) // align < k - 1 or n < k:
+                    continue
+                for hidden in (1, 7):
+                    assert (s1f.partition_ex(n, k, hidden, 1, 1, align)
+                            == P.partition_literal(n, k, hidden, 1, align)), (n, k, hidden, align)
+
+
+@pytest.mark.parametrize("n,k,hidden,align", [(8192, 4, 2560, 1), (32768, 8, 4096, 1), (65536, 16, 7168, 1),
+                                              (131072, 32, 8192, 1), (32768, 8, 4096, 128)])
+def test_partition_ex_literal_full_size_is_optimal(n, k, hidden, align):
+    """At sizes the quadratic oracle cannot reach: the bound T reached is feasible, T - 1 is not (left-to-right
+    greedy: each segment as long as T - 1 allows), and no boundary can move left on its own."""
+    b = s1f.partition_ex(n, k, hidden, 1, s1f.COST_LITERAL, align)
+    assert b[0] == 0 and b[-1] == n and all(x < y for x, y in zip(b[:-1], b[1:]))
+    assert all(x % align == 0 for x in b[1:-1])
+    costs = [P.literal_cost(x, y, hidden) for x, y in zip(b[:-1], b[1:])]
+    T = max(costs)
+
+    def segments_needed(bound):
+        a, used = 0, 0
+        while a < n:
+            # largest y with (y - a)(12 hidden + y) <= bound, by bisection; n itself is always a candidate
+            lo, hi = a, n
+            while lo < hi:
+                mid = (lo + hi + 1) // 2
+                if P.literal_cost(a, mid, hidden) <= bound:
+                    lo = mid
+                else:
+                    hi = mid - 1
+            y = lo if lo == n else lo // align * align
+            if y <= a:
+                return None
+            a, used = y, used + 1
+        return used
+    assert segments_needed(T) <= k
+    fewer = segments_needed(T - 1)
+    assert fewer is None or fewer > k
+    for i in range(1, k):                         # lexicographic minimality, one boundary at a time
+        moved = b[:i] + [b[i] - align] + b[i + 1:]
+        if moved[i] <= moved[i - 1]:
+            continue
+        assert max(P.literal_cost(x, y, hidden) for x, y in zip(moved[:-1], moved[1:])) > T
+
+
+def test_partition_rebalance_matches_oracle():
+    import random
+    rng = random.Random(20240603)
+    for _ in range(200):
+        k = rng.randint(1, 6)
+        align = rng.choice((1, 1, 2, 4, 8))
+        lens = [rng.randint(1, 40) for _ in range(k)]
+        b = [0]
+        for x in lens:
+            b.append(b[-1] + x)
+        cost = [rng.choice((0, rng.randint(1, 1000), rng.randint(1, 10**9))) for _ in range(k)]
+        if sum(cost) == 0 or (b[-1] - 1) // align < k - 1:
+            with pytest.raises(s1f.S1FError):
+                s1f.partition_rebalance(b, cost, align)
+            continue
+        assert s1f.partition_rebalance(b, cost, align) == P.rebalance(b, cost, align), (b, cost, align)
+    assert s1f.partition_rebalance([0, 10, 20, 30], [10, 20, 30]) == [0, 15, 23, 30]
+    assert s1f.partition_rebalance([0, 10, 20, 30], [10, 20, 30], 4) == [0, 16, 24, 30]
+    big = s1f.partition(32768, 8, 4096, 32)
+    ns = [1_900_000_000 + 37 * i for i in range(8)]
+    assert s1f.partition_rebalance(big, ns, 128) == P.rebalance(big, ns, 128)
+
+
+def test_partition_variants_reject_bad_arguments():
+    for bad in ((8, 3, 1, 1, 0, 4), (8, 2, 1, 1, 0, 0), (15, 4, 1, 1, 1, 5), (8, 2, 1, 1, 2, 1), (8, 2, 6, 4, 1, 1)):
+        with pytest.raises(s1f.S1FError) as e:
+            s1f.partition_ex(*bad)
+        assert e.value.status == 1
+    for b, c, a in (([0, 4, 4, 8], [1, 1, 1], 1), ([1, 4, 8], [1, 1], 1), ([0, 4, 8], [0, 0], 1), ([0, 4, 8], [1, -1], 1),
+                    ([0, 4, 8], [1, 1], 0), ([0, 1, 2, 3], [1, 1, 1], 2), ([0, 4, 8], [1 << 48, 1], 1)):
+        with pytest.raises(s1f.S1FError):
+            s1f.partition_rebalance(b, c, a)
+    lib = s1f.load_library()
+    assert lib.s1f_partition_ex(8, 2, 4, 1, 0, 1, None) == 1
+    assert lib.s1f_partition_rebalance(2, None, None, 1, None) == 1
+
+
 def _desc(**kw):
     base = dict(batch=1, n_q_heads=4, n_kv_heads=2, head_dim=64, dtype=1, reserved=0, q_stride_b=4 * 256 * 64,
                 q_stride_h=256 * 64, q_stride_s=64, kv_stride_b=2 * 512 * 64, kv_stride_h=512 * 64, kv_stride_s=64,
