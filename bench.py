@@ -188,6 +188,9 @@ def cache_kernels_report(stage, w, torch, s1f, bounds):
             "bound": "hbm", "peak_GB_per_s": 8000.0, "launches_per_sequence": len(segs)}
 
 
+PP_SIZE, N_MICRO = 4, 16
+
+
 def balance_report(stage, w, seg_ms, bounds, kernels, args):
     """Load balance of the partition (Section 3.4): max/mean over segments of attention time (measured,
     forward + backward of the segment) plus linear-layer time.  The linear layers are not built here: their
@@ -199,7 +202,14 @@ def balance_report(stage, w, seg_ms, bounds, kernels, args):
         rate = tot_att_flops / (sum(att) * 1e-3)                       # FLOP/s achieved on attention
         lin = [72.0 * w.hidden ** 2 * (b - a) / rate * 1e3 for a, b in zip(bnds[:-1], bnds[1:])]
         both = [x + y for x, y in zip(att, lin)]
+        # what the imbalance costs a pipeline: bubble ratio of the sequence-level schedule on PP_SIZE devices with
+        # N_MICRO micro-batches (the paper's 7B setting, Table 1), every stage taking these per-segment times
+        t_f = [int(1e6 * (per_seg_ms["fwd"][i] + lin[i] / 3)) for i in range(len(att))]
+        t_b = [int(1e6 * (per_seg_ms["bwd_dq"][i] + per_seg_ms["bwd_dkdv"][i] + 2 * lin[i] / 3)) for i in range(len(att))]
+        sim = stage.s1f.pipeline_simulate(PP_SIZE, N_MICRO, len(att), 1, t_f, t_b)
+        ideal = (PP_SIZE - 1) / (N_MICRO * len(att) + PP_SIZE - 1)     # equal segments
         return {"attention_only_max_over_mean": max(att) / (sum(att) / len(att)),
+                "pipeline_bubble_ratio": sim["bubble_ratio"], "pipeline_bubble_ratio_equal_segments": ideal,
                 "with_modelled_linear_max_over_mean": max(both) / (sum(both) / len(both)),
                 "attention_total_ms": sum(att), "attention_ms": att, "modelled_linear_ms": lin}
     rep = {"partition": w.partition, "this": ratio(bounds, seg_ms), "linear_term": "modelled, not measured"}

@@ -201,6 +201,62 @@ int s1f_seq1f1b_warmup(int32_t pp_size, int32_t device, int32_t n_micro, int32_t
 int s1f_seq1f1b_order(int32_t pp_size, int32_t device, int32_t n_micro, int32_t n_seg, s1f_pass *order,
                       int64_t capacity, int64_t *n_passes);
 
+/* Interleaved sequence-level schedule (Section 3.3): device i owns the n_chunks stages i, i + P, ..., and
+ * switches to its next stage after P passes.  HOST functions, no device work.
+ *
+ * s1f_seq1f1b_interleaved_warmup writes Eq. 6, (P - i) * 2 + (n_chunks - 1) * P + k - 1 (Eq. 5 when k = 1), capped
+ * at the device's M * k * n_chunks forward passes.
+ * s1f_seq1f1b_interleaved_order writes the device's 2 * M * k * n_chunks passes (kind 0 or 1) in execution order,
+ * sized and reported like s1f_seq1f1b_order.  The paper shows the order in a figure only; the reading built: the
+ * M * k sub-sequences in forward order form groups of P; a group is forwarded through the device's first stage,
+ * then its second, ...; backward passes take the groups in the same order, the stages from last to first, and
+ * inside a group the tail segment of the earliest micro-batch first (Section 3.2's queue); warm-up forward passes,
+ * then one forward and one backward per step, then the remaining backward passes.
+ * Errors: S1F_EINVAL as for s1f_seq1f1b_order or n_chunks < 1; S1F_EUNSUPPORTED unless a group holds whole
+ * micro-batches (k divides P) and P divides M * k. */
+typedef struct {
+  int32_t kind;        /* 0 = forward pass, 1 = backward pass */
+  int32_t micro_batch; /* 0-based */
+  int32_t segment;     /* 0-based */
+  int32_t chunk;       /* 0-based: which of the device's stages; its pipeline stage is chunk * P + i */
+} s1f_stage_pass;
+int s1f_seq1f1b_interleaved_warmup(int32_t pp_size, int32_t device, int32_t n_micro, int32_t n_seg,
+                                   int32_t n_chunks, int64_t *warmup);
+int s1f_seq1f1b_interleaved_order(int32_t pp_size, int32_t device, int32_t n_micro, int32_t n_seg, int32_t n_chunks,
+                                  s1f_stage_pass *order, int64_t capacity, int64_t *n_passes);
+
+/* Timeline of a whole pipeline under these schedules: how long a batch takes, how busy each device is (the bubble
+ * ratio is 1 - sum(busy) / (P * makespan)) and how many intermediate states it holds at its peak (Section 3.1:
+ * warm-up, steady and cooling-down phases; Sections 3.2-3.3; Appendix A.1 for the split backward pass).  HOST
+ * function; times are integers in any one unit.
+ *
+ * Every device walks its order (s1f_seq1f1b_order for n_chunks = 1, s1f_seq1f1b_interleaved_order otherwise;
+ * n_seg = 1 gives 1F1B and 1F1B-I).  A pass starts when the device is free and its input has arrived: a forward
+ * pass needs the sub-sequence forwarded by the previous stage, a backward pass needs it back-propagated by the next
+ * stage (by its own forward pass on the last stage), plus t_comm when that stage is on another device.
+ * split_weight_grad = 1: t_bwd is the input-gradient pass; each leaves a weight-gradient pass of t_wgrad pending,
+ * and a device runs its oldest pending one whenever its next forward or backward pass still waits for its input or
+ * more than max_pending_wgrad are waiting, the rest at the end (a reading: the appendix gives a figure only).
+ * A sub-sequence's states count as held from its forward pass to its backward pass (to its weight-gradient pass
+ * when split).
+ * Results (caller-owned HOST memory): *makespan; busy[P]; peak_live[P] in units of seg_tokens (sub-sequences when
+ * seg_tokens is NULL); peak_pending_wgrad[P] (may be NULL).
+ * Errors: S1F_EINVAL for null pointers, counts < 1, negative or > 2^36 times, reserved != 0, or
+ * M * k * n_chunks * P > 2^24; S1F_EUNSUPPORTED where s1f_seq1f1b_interleaved_order returns it. */
+typedef struct {
+  int32_t pp_size, n_micro, n_seg, n_chunks;
+  int32_t split_weight_grad; /* 0 or 1 */
+  int32_t reserved;          /* must be 0 */
+  int64_t max_pending_wgrad; /* >= 0; only read when split_weight_grad = 1 */
+  int64_t t_comm;            /* >= 0 */
+  const int64_t *t_fwd;      /* [n_seg] forward pass of segment j on one stage */
+  const int64_t *t_bwd;      /* [n_seg] */
+  const int64_t *t_wgrad;    /* [n_seg], or NULL when split_weight_grad = 0 */
+  const int64_t *seg_tokens; /* [n_seg] weights of the held states, or NULL for 1 each */
+} s1f_pipeline_desc;
+int s1f_pipeline_simulate(const s1f_pipeline_desc *desc, int64_t *makespan, int64_t *busy, int64_t *peak_live,
+                          int64_t *peak_pending_wgrad);
+
 /* Static, NUL-terminated description of a status code. */
 const char *s1f_strerror(int status);
 

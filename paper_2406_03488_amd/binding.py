@@ -30,6 +30,20 @@ class Pass(ctypes.Structure):
     _fields_ = [("micro_batch", ctypes.c_int32), ("segment", ctypes.c_int32), ("backward", ctypes.c_int32)]
 
 
+class StagePass(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("micro_batch", ctypes.c_int32), ("segment", ctypes.c_int32),
+                ("chunk", ctypes.c_int32)]
+
+
+class PipelineDesc(ctypes.Structure):
+    """Mirror of s1f_pipeline_desc."""
+    _fields_ = [("pp_size", ctypes.c_int32), ("n_micro", ctypes.c_int32), ("n_seg", ctypes.c_int32),
+                ("n_chunks", ctypes.c_int32), ("split_weight_grad", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("max_pending_wgrad", ctypes.c_int64), ("t_comm", ctypes.c_int64),
+                ("t_fwd", ctypes.POINTER(ctypes.c_int64)), ("t_bwd", ctypes.POINTER(ctypes.c_int64)),
+                ("t_wgrad", ctypes.POINTER(ctypes.c_int64)), ("seg_tokens", ctypes.POINTER(ctypes.c_int64))]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -69,6 +83,14 @@ def load_library():
     lib.s1f_seq1f1b_warmup.restype = ctypes.c_int
     lib.s1f_seq1f1b_order.argtypes = [i32, i32, i32, i32, ctypes.POINTER(Pass), i64, ctypes.POINTER(i64)]
     lib.s1f_seq1f1b_order.restype = ctypes.c_int
+    lib.s1f_seq1f1b_interleaved_warmup.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(i64)]
+    lib.s1f_seq1f1b_interleaved_warmup.restype = ctypes.c_int
+    lib.s1f_seq1f1b_interleaved_order.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(StagePass), i64,
+                                                  ctypes.POINTER(i64)]
+    lib.s1f_seq1f1b_interleaved_order.restype = ctypes.c_int
+    lib.s1f_pipeline_simulate.argtypes = [ctypes.POINTER(PipelineDesc), ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                          ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.s1f_pipeline_simulate.restype = ctypes.c_int
     lib.s1f_strerror.argtypes = [ctypes.c_int]
     lib.s1f_strerror.restype = ctypes.c_char_p
     lib.s1f_version.argtypes = []
@@ -141,6 +163,52 @@ def seq1f1b_order(pp_size: int, device: int, n_micro: int, n_seg: int):
     if rc != 0:
         raise S1FError(rc, "s1f_seq1f1b_order")
     return [("B" if buf[i].backward else "F", int(buf[i].micro_batch), int(buf[i].segment)) for i in range(n.value)]
+
+
+def seq1f1b_interleaved_warmup(pp_size: int, device: int, n_micro: int, n_seg: int, n_chunks: int) -> int:
+    """s1f_seq1f1b_interleaved_warmup: sub-sequences forwarded before the first backward pass (Eq. 5-6)."""
+    w = ctypes.c_int64(0)
+    rc = load_library().s1f_seq1f1b_interleaved_warmup(int(pp_size), int(device), int(n_micro), int(n_seg),
+                                                       int(n_chunks), ctypes.byref(w))
+    if rc != 0:
+        raise S1FError(rc, "s1f_seq1f1b_interleaved_warmup")
+    return int(w.value)
+
+
+def seq1f1b_interleaved_order(pp_size: int, device: int, n_micro: int, n_seg: int, n_chunks: int):
+    """s1f_seq1f1b_interleaved_order: list of ("F" | "B", micro_batch, segment, chunk) in execution order."""
+    n = ctypes.c_int64(0)
+    cap = 2 * max(int(n_micro), 0) * max(int(n_seg), 0) * max(int(n_chunks), 0)
+    buf = (StagePass * max(cap, 1))()
+    rc = load_library().s1f_seq1f1b_interleaved_order(int(pp_size), int(device), int(n_micro), int(n_seg),
+                                                      int(n_chunks), buf, cap, ctypes.byref(n))
+    if rc != 0:
+        raise S1FError(rc, "s1f_seq1f1b_interleaved_order")
+    return [("B" if buf[i].kind else "F", int(buf[i].micro_batch), int(buf[i].segment), int(buf[i].chunk))
+            for i in range(n.value)]
+
+
+def pipeline_simulate(pp_size: int, n_micro: int, n_seg: int, n_chunks: int, t_fwd, t_bwd, t_wgrad=None,
+                      t_comm: int = 0, max_pending_wgrad: int = 0, seg_tokens=None):
+    """s1f_pipeline_simulate: dict with makespan, busy, peak_live, peak_pending (lists over devices) and the
+    bubble ratio 1 - sum(busy) / (P * makespan) derived from them."""
+    k, P = int(n_seg), int(pp_size)
+    if k < 1 or P < 1 or len(t_fwd) != k or len(t_bwd) != k or (t_wgrad is not None and len(t_wgrad) != k) or (
+            seg_tokens is not None and len(seg_tokens) != k):
+        raise S1FError(1, "s1f_pipeline_simulate")
+    arr = lambda xs: (ctypes.c_int64 * k)(*[int(x) for x in xs])
+    keep = [arr(t_fwd), arr(t_bwd), arr(t_wgrad) if t_wgrad is not None else None,
+            arr(seg_tokens) if seg_tokens is not None else None]
+    desc = PipelineDesc(P, int(n_micro), k, int(n_chunks), 1 if t_wgrad is not None else 0, 0, int(max_pending_wgrad),
+                        int(t_comm), keep[0], keep[1], keep[2], keep[3])
+    span = ctypes.c_int64(0)
+    busy, live, pend = ((ctypes.c_int64 * P)() for _ in range(3))
+    rc = load_library().s1f_pipeline_simulate(ctypes.byref(desc), ctypes.byref(span), busy, live, pend)
+    if rc != 0:
+        raise S1FError(rc, "s1f_pipeline_simulate")
+    out = {"makespan": int(span.value), "busy": list(busy), "peak_live": list(live), "peak_pending": list(pend)}
+    out["bubble_ratio"] = 1.0 - sum(out["busy"]) / (P * out["makespan"]) if out["makespan"] > 0 else 0.0
+    return out
 
 
 def _dtype_code(t):

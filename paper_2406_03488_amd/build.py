@@ -10,7 +10,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libs1f.so")
 PROBE_LIB = os.path.join(HERE, "libs1f_probe.so")   # measurement aid used by bench.py only
 
-SOURCES = ["s1f_api.hip", "s1f_cache.hip", "s1f_partition.cpp", "s1f_schedule.cpp"]
+SOURCES = ["s1f_api.hip", "s1f_cache.hip", "s1f_partition.cpp", "s1f_schedule.cpp", "s1f_pipeline.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
          # packed fp32 VALU forms are kept out of generated code on this target
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -1,0 +1,104 @@
+"""CPU-only parity of the pipeline calculators of the library (interleaved warm-up counts and order, the timeline
+of all devices) with the oracle: integer results, compared exactly."""
+import itertools
+import random
+
+import pytest
+
+import paper_2406_03488_amd as s1f
+from oracle import pipeline as PL
+
+
+def test_interleaved_warmup_matches_oracle():
+    for P, M, k, n in itertools.product((1, 2, 4, 8), (1, 2, 8, 16), (1, 2, 4, 8), (1, 2, 3)):
+        for i in range(1, P + 1):
+            assert s1f.seq1f1b_interleaved_warmup(P, i, M, k, n) == PL.interleaved_warmup(P, i, M, k, n)
+
+
+@pytest.mark.parametrize("P,M,k,n", [(2, 2, 1, 2), (2, 4, 2, 2), (4, 8, 1, 2), (4, 8, 2, 2), (4, 8, 4, 2), (4, 6, 2, 3),
+                                      (8, 4, 4, 2), (8, 8, 8, 2), (4, 1, 4, 2), (1, 3, 1, 2), (4, 4, 1, 4), (8, 16, 4, 2)])
+def test_interleaved_order_matches_oracle(P, M, k, n):
+    for i in range(1, P + 1):
+        assert s1f.seq1f1b_interleaved_order(P, i, M, k, n) == PL.interleaved_order(P, i, M, k, n)
+
+
+def test_interleaved_order_errors():
+    for P, M, k, n in ((4, 8, 8, 2), (4, 4, 3, 2), (4, 3, 2, 2), (8, 3, 4, 2)):
+        with pytest.raises(s1f.S1FError) as e:
+            s1f.seq1f1b_interleaved_order(P, 1, M, k, n)
+        assert e.value.status == 2          # unsupported: a group would split a micro-batch
+    for bad in ((0, 1, 4, 1, 2), (4, 0, 4, 1, 2), (4, 5, 4, 1, 2), (4, 1, 0, 1, 2), (4, 1, 4, 0, 2), (4, 1, 4, 1, 0)):
+        with pytest.raises(s1f.S1FError) as e:
+            s1f.seq1f1b_interleaved_order(*bad)
+        assert e.value.status == 1
+        with pytest.raises(s1f.S1FError):
+            s1f.seq1f1b_interleaved_warmup(*bad)
+
+
+def _compare(P, M, k, n, tf, tb, tw, comm, cap, tok):
+    got = s1f.pipeline_simulate(P, M, k, n, tf, tb, tw, comm, cap, tok)
+    want = PL.simulate(P, n, PL.device_orders(P, M, k, n), tf, tb, tw, comm, cap, tok)
+    assert want is not None
+    for key in ("makespan", "busy", "peak_live", "peak_pending"):
+        assert got[key] == want[key], (key, P, M, k, n, tf, tb, tw, comm, cap, tok)
+    assert abs(got["bubble_ratio"] - PL.bubble_ratio(want, P)) < 1e-12
+
+
+def test_timeline_matches_oracle_hand_cases(golden_dir):
+    for line in open(f"{golden_dir}/pipeline_tiny.txt"):
+        if line.startswith("timeline "):
+            args, want = line[len("timeline"):].split(":")
+            P, M, k, n, tf, tb, comm = (int(x) for x in args.split())
+            r = s1f.pipeline_simulate(P, M, k, n, [tf] * k, [tb] * k, None, comm)
+            assert [r["makespan"], *r["busy"]] == [int(x) for x in want.split()]
+
+
+def test_timeline_matches_oracle_random():
+    rng = random.Random(2406)
+    done = 0
+    while done < 150:
+        P = rng.choice((1, 2, 3, 4, 8))
+        k = rng.choice((1, 2, 3, 4, 8))
+        n = rng.choice((1, 1, 2, 3))
+        M = rng.randint(1, 10)
+        if n > 1 and ((M * k) % P or P % k):
+            continue
+        tf = [rng.randint(0, 40) for _ in range(k)]
+        tb = [rng.randint(0, 80) for _ in range(k)]
+        tw = [rng.randint(0, 40) for _ in range(k)] if rng.random() < 0.5 else None
+        tok = [rng.randint(0, 9000) for _ in range(k)] if rng.random() < 0.5 else None
+        _compare(P, M, k, n, tf, tb, tw, rng.choice((0, 0, 3, 25)), rng.choice((0, 1, 2, 5, 10**6)), tok)
+        done += 1
+
+
+def test_timeline_contract_workload_shapes():
+    # the 7b setting of the paper's Table 1 at 32k tokens: P = 4, 16 micro-batches, k = 8 computation-wise segments;
+    # per-segment times in microseconds of the order this library measures for attention plus modelled linear layers
+    k = 8
+    tf = [2100 + 15 * j for j in range(k)]
+    tb = [4300 + 25 * j for j in range(k)]
+    _compare(4, 16, k, 1, tf, tb, None, 40, 0, [6076, 5056, 4424, 3983, 3652, 3392, 3181, 3004])
+    k = 4
+    tf, tb, tw = [4000] * k, [4100] * k, [3900] * k
+    _compare(4, 16, k, 2, tf, tb, tw, 40, 2, None)
+    seq = s1f.pipeline_simulate(4, 16, 4, 1, [4000] * 4, [8000] * 4)
+    plain = s1f.pipeline_simulate(4, 16, 1, 1, [16000], [32000])
+    inter = s1f.pipeline_simulate(4, 16, 4, 2, [2000] * 4, [4000] * 4)
+    assert inter["bubble_ratio"] < seq["bubble_ratio"] < plain["bubble_ratio"]        # Section 3.3's ranking
+    assert abs(plain["bubble_ratio"] - 3 / 19) < 1e-12 and abs(seq["bubble_ratio"] - 3 / 67) < 1e-12
+
+
+def test_timeline_errors():
+    ok = dict(pp_size=4, n_micro=8, n_seg=2, n_chunks=1, t_fwd=[1, 1], t_bwd=[2, 2])
+    assert s1f.pipeline_simulate(**ok)["makespan"] > 0
+    for patch in (dict(pp_size=0), dict(n_micro=0), dict(n_chunks=0), dict(t_fwd=[1, -1]), dict(t_bwd=[1, 1 << 40]),
+                  dict(t_comm=-1), dict(t_wgrad=[1, 1], max_pending_wgrad=-1), dict(t_fwd=[1]), dict(seg_tokens=[1, -2]),
+                  dict(n_micro=1 << 20, n_seg=2, pp_size=64)):
+        with pytest.raises(s1f.S1FError) as e:
+            s1f.pipeline_simulate(**{**ok, **patch})
+        assert e.value.status == 1
+    with pytest.raises(s1f.S1FError) as e:
+        s1f.pipeline_simulate(**{**ok, "n_chunks": 2, "n_seg": 3, "t_fwd": [1] * 3, "t_bwd": [1] * 3})
+    assert e.value.status == 2
+    lib = s1f.load_library()
+    assert lib.s1f_pipeline_simulate(None, None, None, None, None) == 1
