@@ -57,24 +57,27 @@ def seg_pairs(bounds):
 
 def measured_mfma_peak(torch):
     """TFLOP/s of register-resident back-to-back v_mfma_f32_32x32x16_bf16 on every SIMD (two waves per SIMD),
-    measured in this run with the probe kernel of libs1f_probe.so."""
+    measured in this run with the probe kernel of libs1f_probe.so: (constant operands, operands that change from
+    instruction to instruction).  The second is the rate the matrix pipe sustains under the chip's power limit
+    when the data toggles like real activations."""
     import ctypes
     lib = ctypes.CDLL(os.path.join(ROOT, "paper_2406_03488_amd", "libs1f_probe.so"))
-    lib.s1f_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    lib.s1f_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     lib.s1f_probe_mfma_bf16.restype = ctypes.c_int
     wgs, iters = 512, 4000
     sink = torch.zeros(wgs * 256, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
-    best = 0.0
-    for rep in range(3):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        if lib.s1f_probe_mfma_bf16(wgs, iters, sink.data_ptr(), stream) != 0:
-            raise RuntimeError("matrix-peak probe failed to launch")
-        e1.record()
-        torch.cuda.synchronize()
-        flops = wgs * 4 * 16.0 * iters * 32768.0
-        best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    best = [0.0, 0.0]
+    for varied in (0, 1):
+        for rep in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            if lib.s1f_probe_mfma_bf16(wgs, iters, varied, sink.data_ptr(), stream) != 0:
+                raise RuntimeError("matrix-peak probe failed to launch")
+            e1.record()
+            torch.cuda.synchronize()
+            flops = wgs * 4 * 16.0 * iters * 32768.0
+            best[varied] = max(best[varied], flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
     return best
 
 
@@ -336,10 +339,13 @@ def main():
     result["step_ms_mean"] = mean
     result["step_ms_std"] = (sum((x - mean) ** 2 for x in sm) / max(1, len(sm) - 1)) ** 0.5
     if not args.no_mfma_probe and w.dtype == "bf16":
-        mp = measured_mfma_peak(torch)
+        mp, mp_varied = measured_mfma_peak(torch)
         result["measured_mfma_peak_tflops"] = mp
+        result["measured_mfma_peak_varied_data_tflops"] = mp_varied
         result["pct_of_measured_peak"] = 100.0 * result["value"] / mp
+        result["pct_of_measured_peak_varied_data"] = 100.0 * result["value"] / mp_varied
         roofline["frac_of_measured_peak"] = roofline["achieved"] / mp
+        roofline["frac_of_measured_peak_varied_data"] = roofline["achieved"] / mp_varied
     result["cache_kernels"] = cache_kernels_report(stage, w, torch, s1f, bounds)
     if not args.no_balance:
         result["balance"] = balance_report(stage, w, seg_ms, bounds, kernels, args)
