@@ -31,6 +31,7 @@ def parse():
     ap.add_argument("--workload", default="7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unsegmented", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the replay of the step recorded as one HIP graph")
     ap.add_argument("--no-balance", action="store_true", help="skip the cwp-vs-uniform load-balance report")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the measured matrix-peak microbenchmark")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -242,6 +243,24 @@ def balance_report(stage, w, seg_ms, bounds, kernels, args):
     return rep
 
 
+def graph_report(stage, torch, flops, steps):
+    """The same step recorded once as a HIP graph and replayed `steps` times: what the launches cost on top of the
+    kernels (it matters for the small workloads, whose step is 24 launches of ~0.1 ms)."""
+    stage.step()                      # warm: every kernel has run once outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        stage.step()
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    return {"ms_per_step": ms, "tflops": flops / (ms * 1e-3) / 1e12}
+
+
 def cpu_baseline(stage, torch):
     """The row oracle, as it stands, timed on this machine's host cores on a bounded sample of the workload:
     the first `ns` tokens of a few heads, full causal forward + backward (about 5e8 (query, key) pairs)."""
@@ -354,6 +373,8 @@ def main():
         ms1 = stage.run(max(2, args.steps // 3), 1, n_seg=1, kind="uniform")
         result["unsegmented_ms"] = ms1
         result["segmentation_overhead"] = ms / ms1 - 1.0
+    if not args.no_graph:
+        result["hip_graph"] = graph_report(stage, torch, flops, args.steps)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(stage, torch)
     print(json.dumps(result))
