@@ -156,6 +156,7 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
   // no matrix instruction: two instances of the whole step (with and without mask code) in one loop body make
   // the compiler keep the output accumulators in two places and copy all 64 registers on every step.
   if (HAS_NEXT && mask_next) {
+    asm volatile("" ::: "memory");   // keeps this a branch: turned into selects it would run on every step
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
@@ -235,6 +236,14 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
       ld.issue_part(step_part * (LD::PARTS / KB) + p, kbase, vbase, a.kv_ss, jt * BN, kv_len,
                     lds0 + (jt % 3) * Cfg::STAGE_BYTES, wave, lane);
   };
+  // The same for the tile whose first row `krow`/`vrow` point at and whose ring stage is known: the steady loop
+  // keeps these running instead of deriving them from the tile number on every step.
+  auto issue_part_at = [&](const T *krow, const T *vrow, int rows_left, int stage, int step_part) {
+#pragma unroll
+    for (int p = 0; p < LD::PARTS / KB; ++p)
+      ld.issue_part(step_part * (LD::PARTS / KB) + p, krow, vrow, a.kv_ss, 0, rows_left,
+                    lds0 + stage * Cfg::STAGE_BYTES, wave, lane);
+  };
   auto issue = [&](int jt) {
 #pragma unroll
     for (int p = 0; p < KB; ++p) issue_part(jt, p);
@@ -290,28 +299,42 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
 #define S1F_TRACE_ARGS
 #endif
   int k = 0;
+  // Ring stages of the tiles holding block k (st_cur) and block k + 1 (st_next), and the tile that the next copy
+  // fills: its first K and V rows, the rows of the prefix from there on, its stage.
+  int st_cur = 0, st_next = KB == 1 ? 1 : 0;
+  int jt_iss = 2, st_iss = 2, rows_iss = kv_len - 2 * BN;
+  const T *k_iss = kbase + (int64_t)(2 * BN) * a.kv_ss, *v_iss = vbase + (int64_t)(2 * BN) * a.kv_ss;
   while (true) {
     bool raise_any = false;
     while (k + 1 < n_blk) {
-      const int jt = k / KB, kb = k % KB;
+      const int kb = k % KB;
       S1F_TRACE_MARK(0);
       if (kb == KB - 1) {
-        wait_async_tiles();   // this wave's part of tile jt+1 has landed (it was issued a whole tile ago)
+        wait_async_tiles();   // this wave's part of the next tile has landed (it was issued a whole tile ago)
 #ifdef S1F_TRACE
         S1F_TRACE_MARK(5);
 #endif
-        __syncthreads();      // ... and everyone's; every wave has also finished reading tile jt-1
+        __syncthreads();      // ... and everyone's; every wave has also finished reading the previous tile
         S1F_TRACE_MARK(6);
       }
-      // tile jt+2 (for kb = KB-1; the later parts follow in the steps of tile jt+1) goes to the stage of tile jt-1
+      // the tile two ahead of block k's (for kb = KB-1; the later parts follow in the steps of the next tile) goes
+      // to the stage of the tile before block k's
       {
-        const int part = (kb + 1) % KB, jt_new = kb == KB - 1 ? jt + 2 : jt + 1;
-        if (jt_new >= 2 && jt_new < n_kt) issue_part(jt_new, part);
+        const int part = (kb + 1) % KB;
+        const bool copying = KB == 1 || k > 0;   // tiles 0 and 1 were copied whole before the loop
+        if (copying && jt_iss < n_kt) issue_part_at(k_iss, v_iss, rows_iss, st_iss, part);
+        if (copying && part == KB - 1) {   // that tile's copy is complete: move on to the following one
+          ++jt_iss;
+          st_iss = st_iss == 2 ? 0 : st_iss + 1;
+          rows_iss -= BN;
+          k_iss += (int64_t)BN * a.kv_ss;
+          v_iss += (int64_t)BN * a.kv_ss;
+        }
       }
       S1F_TRACE_MARK(1);
-      const lds_addr vblock = lds0 + (jt % 3) * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
+      const lds_addr vblock = lds0 + st_cur * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
       const int kn = k + 1;
-      const lds_addr kblock_next = lds0 + ((kn / KB) % 3) * Cfg::STAGE_BYTES + (kn % KB) * BLOCK_BYTES;
+      const lds_addr kblock_next = lds0 + st_next * Cfg::STAGE_BYTES + (kn % KB) * BLOCK_BYTES;
       const int lim0n = seg_off + wrow0 + ln - 32 * kn - 4 * g;
       // the last block always crosses the diagonal; earlier ones do if their last key is past the wave's first row
       const bool mask_next = kn + 1 == n_blk || 32 * kn + 31 > seg_off + wrow0;
@@ -324,6 +347,8 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
       }
 #endif
       k = kn;
+      st_cur = st_next;
+      if ((k + 1) % KB == 0) st_next = st_next == 2 ? 0 : st_next + 1;
       bool raise = false;
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
@@ -344,8 +369,7 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
     }
   }
   {   // last block: no next scores to compute
-    const int jt = k / KB, kb = k % KB;
-    const lds_addr vblock = lds0 + (jt % 3) * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
+    const lds_addr vblock = lds0 + st_cur * Cfg::STAGE_BYTES + KT::BYTES + (k % KB) * BLOCK_BYTES;
     fwd_step<RD, T, false>(s, sn, o, m, l, mx, qf, rd, vblock, vblock, c, false, 0 S1F_TRACE_ARGS);
   }
 
