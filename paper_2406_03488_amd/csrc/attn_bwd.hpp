@@ -53,7 +53,7 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int qt, bh;
-  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, qt, bh);
+  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
   qt = a.n_tiles - 1 - qt;   // later (heavier) row tiles are scheduled first
   const int h = bh % a.n_q_heads, b = bh / a.n_q_heads, hk = h / a.group;
   const int seg_off = a.seg_off, seg_len = a.seg_len, kv_len = seg_off + seg_len;
@@ -244,7 +244,7 @@ __global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kerne
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int kt, bh;
-  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, kt, bh);   // early key tiles see every query row: heaviest first
+  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, a.tile_major, kt, bh);   // early key tiles see every query row: heaviest first
   const int n_kv_heads = a.n_q_heads / a.group;
   const int hk = bh % n_kv_heads, b = bh / n_kv_heads;
   const int seg_off = a.seg_off, seg_len = a.seg_len, kv_len = seg_off + seg_len;

@@ -445,14 +445,23 @@ template <> S1F_DEV void store4<bf16_t>(bf16_t *p, float a, float b, float c, fl
 
 // Workgroup id -> (tile, batch*head).  The hardware hands consecutive workgroup ids to the 8 XCDs in turn,
 // and each XCD has its own L2.  All tiles of one (batch, head) stream the same K/V prefix (or the same
-// Q/dO segment), so they are given ids that land on one XCD, next to each other in time: the shared
-// operand is then fetched from HBM once per XCD instead of once per workgroup.  Falls back to the plain
-// order when the number of (batch, head) pairs is not a multiple of 8.
-S1F_DEV void decode_workgroup(int id, int n_tiles, int n_bh, int &tile, int &bh) {
+// Q/dO segment), so they are given ids that land on one XCD: the shared operand is then fetched from HBM once
+// per XCD instead of once per workgroup.  Within an XCD the ids run head by head (`tile_major` = 0: best when
+// the tiles of a launch take about the same time, i.e. behind a long prefix) or tile by tile over the XCD's
+// heads (`tile_major` = 1: the light tiles of every head come last, which shortens the end of a launch whose
+// tiles differ a lot, i.e. the first segments).  Falls back to the plain order when the number of (batch, head)
+// pairs is not a multiple of 8.
+S1F_DEV void decode_workgroup(int id, int n_tiles, int n_bh, int tile_major, int &tile, int &bh) {
   if ((n_bh & 7) == 0) {
     const int xcd = id & 7, slot = id >> 3;
-    bh = xcd + 8 * (slot / n_tiles);
-    tile = slot % n_tiles;
+    if (tile_major) {
+      const int per_xcd = n_bh >> 3;
+      bh = xcd + 8 * (slot % per_xcd);
+      tile = slot / per_xcd;
+    } else {
+      bh = xcd + 8 * (slot / n_tiles);
+      tile = slot % n_tiles;
+    }
   } else {
     bh = id / n_tiles;
     tile = id % n_tiles;
@@ -473,6 +482,7 @@ struct AttnArgs {
   int32_t seg_off, seg_len;
   int32_t n_q_heads, group;              // group = Hq / Hkv
   int32_t n_tiles, n_bh;                 // launch shape: tiles per (batch, head) and number of (batch, head) pairs
+  int32_t tile_major;                    // order of the workgroups within an XCD (see decode_workgroup)
   float scale;                           // 1/sqrt(head_dim)
 #ifdef S1F_TRACE
   unsigned long long *trace;             // development aid: cycle stamps of one wave

@@ -208,7 +208,7 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int qt, bh;
-  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, qt, bh);
+  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
   qt = a.n_tiles - 1 - qt;   // later (heavier) row tiles are scheduled first
   const int h = bh % a.n_q_heads, b = bh / a.n_q_heads, hk = h / a.group;
   const int seg_off = a.seg_off, seg_len = a.seg_len, kv_len = seg_off + seg_len;

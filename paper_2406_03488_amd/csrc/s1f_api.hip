@@ -58,10 +58,13 @@ AttnArgs make_args(const s1f_desc *d, int64_t seg_off, int64_t seg_len) {
 }
 
 // One-dimensional grid of n_tiles * n_bh workgroups; the kernels decode (tile, batch*head) themselves.
-template <typename K> int launch(K kernel, int n_tiles, int n_bh, int threads, int lds_bytes, AttnArgs a, hipStream_t st) {
+// `tile_major`: order of the workgroups within an XCD; chosen per kernel from the shape of the segment.
+template <typename K>
+int launch(K kernel, int n_tiles, int n_bh, int tile_major, int threads, int lds_bytes, AttnArgs a, hipStream_t st) {
   if ((int64_t)n_tiles * n_bh > 0x7fffffff) return S1F_EUNSUPPORTED;
   a.n_tiles = n_tiles;
   a.n_bh = n_bh;
+  a.tile_major = tile_major;
   const dim3 grid((unsigned)((int64_t)n_tiles * n_bh));
   if (lds_bytes > 64 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -76,14 +79,14 @@ template <typename T, int D> int fwd_impl(const s1f_desc *d, const AttnArgs &a, 
   typedef Shape<T> S;
   typedef FwdCfg<T, D, S::FNQ, S::FKB, S::FNW> Cfg;
   return launch(seg_attn_fwd_kernel<T, D, S::FNQ, S::FKB, S::FNW, S::FOCC>, (a.seg_len + Cfg::BM - 1) / Cfg::BM,
-                d->n_q_heads * d->batch, Cfg::THREADS, Cfg::LDS_BYTES, a, st);
+                d->n_q_heads * d->batch, (int64_t)a.seg_off < 2 * (int64_t)a.seg_len, Cfg::THREADS, Cfg::LDS_BYTES, a, st);
 }
 
 template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
   typedef Shape<T> S;
   typedef BwdDqCfg<T, D, S::QNQ, S::QBN> QC;
   return launch(seg_attn_bwd_dq_kernel<T, D, S::QNQ, S::QBN, S::QOCC>, (a.seg_len + QC::BM - 1) / QC::BM,
-                d->n_q_heads * d->batch, 256, QC::LDS_BYTES, a, st);
+                d->n_q_heads * d->batch, (int64_t)a.seg_off < 2 * (int64_t)a.seg_len, 256, QC::LDS_BYTES, a, st);
 }
 
 template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
@@ -91,7 +94,7 @@ template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs
   typedef BwdDkdvCfg<T, D, S::KNW, S::KDIST, S::KLAG> KC;
   const int kv_len = a.seg_off + a.seg_len;
   return launch(seg_attn_bwd_dkdv_kernel<T, D, S::KNW, S::KDIST, S::KLAG>, (kv_len + KC::BNW - 1) / KC::BNW,
-                d->n_kv_heads * d->batch, KC::THREADS, KC::LDS_BYTES, a, st);
+                d->n_kv_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, KC::THREADS, KC::LDS_BYTES, a, st);
 }
 
 
