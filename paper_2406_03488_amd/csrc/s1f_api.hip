@@ -79,14 +79,14 @@ template <typename T, int D> int fwd_impl(const s1f_desc *d, const AttnArgs &a, 
   typedef Shape<T> S;
   typedef FwdCfg<T, D, S::FNQ, S::FKB, S::FNW> Cfg;
   return launch(seg_attn_fwd_kernel<T, D, S::FNQ, S::FKB, S::FNW, S::FOCC>, (a.seg_len + Cfg::BM - 1) / Cfg::BM,
-                d->n_q_heads * d->batch, (int64_t)a.seg_off < 2 * (int64_t)a.seg_len, Cfg::THREADS, Cfg::LDS_BYTES, a, st);
+                d->n_q_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, Cfg::THREADS, Cfg::LDS_BYTES, a, st);
 }
 
 template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
   typedef Shape<T> S;
   typedef BwdDqCfg<T, D, S::QNQ, S::QBN> QC;
   return launch(seg_attn_bwd_dq_kernel<T, D, S::QNQ, S::QBN, S::QOCC>, (a.seg_len + QC::BM - 1) / QC::BM,
-                d->n_q_heads * d->batch, (int64_t)a.seg_off < 2 * (int64_t)a.seg_len, 256, QC::LDS_BYTES, a, st);
+                d->n_q_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, 256, QC::LDS_BYTES, a, st);
 }
 
 template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
