@@ -370,9 +370,14 @@ def main():
         result["balance"] = balance_report(stage, w, seg_ms, bounds, kernels, args)
     if not args.no_unsegmented:
         stage.events = []
-        ms1 = stage.run(max(2, args.steps // 3), 1, n_seg=1, kind="uniform")
+        steps1 = max(2, args.steps // 3)
+        ms1 = stage.run(steps1, 1, n_seg=1, kind="uniform")
         result["unsegmented_ms"] = ms1
         result["segmentation_overhead"] = ms / ms1 - 1.0
+        per_kernel = {}
+        for kind, _, e0, e1 in stage.events:
+            per_kernel[kind] = per_kernel.get(kind, 0.0) + e0.elapsed_time(e1) / steps1
+        result["unsegmented_kernels_ms"] = per_kernel   # against kernels[*].ms_per_step: where the overhead sits
     if not args.no_graph:
         result["hip_graph"] = graph_report(stage, torch, flops, args.steps)
     if not args.no_cpu_baseline:
