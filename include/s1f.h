@@ -56,8 +56,9 @@ typedef struct {
   int32_t head_dim;   /* 64, 80 or 128 */
   int32_t dtype;      /* s1f_dtype; lse and the dK/dV accumulators are always fp32 */
   int32_t reserved;   /* must be 0 */
-  int64_t q_stride_b, q_stride_h, q_stride_s;    /* elements; q_stride_s >= head_dim */
-  int64_t kv_stride_b, kv_stride_h, kv_stride_s; /* elements; kv_stride_s >= head_dim */
+  int64_t q_stride_b, q_stride_h, q_stride_s;    /* elements; head_dim <= q_stride_s < 2^23 */
+  int64_t kv_stride_b, kv_stride_h, kv_stride_s; /* elements; head_dim <= kv_stride_s < 2^23 (the kernels' asynchronous
+                                                    copies use 32-bit byte offsets inside a tile; S1F_EUNSUPPORTED beyond) */
   int64_t kv_capacity; /* rows allocated per head in k, v, dk_prefix_acc, dv_prefix_acc */
 } s1f_desc;
 
@@ -132,8 +133,8 @@ int s1f_seg_attn_fwd(const s1f_desc *desc, const void *q_seg, const void *k_pref
  *             (two fp32 values per query row and head: -lse/scale and -rowsum(dout * out), the row
  *             statistics the dK/dV kernel starts its products from); contents are undefined afterwards.
  * Errors as above, plus S1F_EINVAL if workspace is NULL or workspace_bytes is too small, and
- * S1F_EUNSUPPORTED if q_stride_s >= 2^23 elements or batch * n_q_heads * seg_len > 2^28 (the kernels'
- * asynchronous copies use 32-bit byte offsets inside a tile and inside the workspace). */
+ * S1F_EUNSUPPORTED if batch * n_q_heads * seg_len > 2^28 (the kernels' asynchronous copies use 32-bit byte
+ * offsets inside the workspace). */
 int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
                      const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
                      int64_t seg_len, void *dq, float *dk_prefix_acc, float *dv_prefix_acc,

@@ -38,6 +38,8 @@ int check_desc(const s1f_desc *d) {
   for (int i = 0; i < 6; ++i)
     if (s[i] < 0 || s[i] % ce != 0) return S1F_EINVAL;
   if (d->q_stride_s < d->head_dim || d->kv_stride_s < d->head_dim) return S1F_EINVAL;
+  // the asynchronous tile copies address the rows of a tile (up to 64 rows) with 32-bit byte offsets
+  if (d->q_stride_s >= (int64_t(1) << 23) || d->kv_stride_s >= (int64_t(1) << 23)) return S1F_EUNSUPPORTED;
   return S1F_OK;
 }
 
@@ -153,9 +155,8 @@ int bwd_prepare(const s1f_desc *desc, const void *dout, const void *q_seg, const
   rc = check_seg(desc, seg_off, seg_len);
   if (rc != S1F_OK) return rc;
   if (workspace_bytes < s1f_bwd_workspace_bytes(desc, seg_off, seg_len)) return S1F_EINVAL;
-  // the asynchronous copies address rows of a Q/dO tile and the workspace with 32-bit byte offsets
-  if (desc->q_stride_s >= (int64_t(1) << 23) || desc->batch * desc->n_q_heads * seg_len > (int64_t(1) << 28))
-    return S1F_EUNSUPPORTED;
+  // the asynchronous copies address the workspace with 32-bit byte offsets
+  if (desc->batch * desc->n_q_heads * seg_len > (int64_t(1) << 28)) return S1F_EUNSUPPORTED;
   *a = make_args(desc, seg_off, seg_len);
   a->q = q_seg; a->k = k_prefix; a->v = v_prefix; a->dout = dout;
   a->lse = const_cast<float *>(lse);

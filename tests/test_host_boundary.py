@@ -175,6 +175,8 @@ def test_attention_entry_points_validate_before_any_launch():
     assert fwd(_desc(reserved=1)) == 1
     assert fwd(_desc(head_dim=96)) == 2
     assert fwd(_desc(dtype=7)) == 2
+    assert fwd(_desc(kv_stride_s=1 << 23, kv_stride_h=1 << 40, kv_stride_b=1 << 41)) == 2   # row stride beyond the kernels' reach
+    assert fwd(_desc(q_stride_s=1 << 23, q_stride_h=1 << 40, q_stride_b=1 << 41)) == 2
     assert fwd(_desc(), seg_off=-1) == 3
     assert fwd(_desc(), seg_len=0) == 3
     assert fwd(_desc(), seg_off=300, seg_len=256) == 3            # past kv_capacity
