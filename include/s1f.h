@@ -14,15 +14,19 @@
  *
  * Conventions common to all device entry points
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library allocates nothing,
- *     keeps no pointer after return, and has no global state (re-entrant).
+ *     keeps no pointer after return, and has no global state beyond a per-device "large LDS enabled" flag
+ *     per kernel (re-entrant).
  *   - Layout is [batch, head, sequence, head_dim] with head_dim contiguous; the other three strides
  *     are passed in ELEMENTS through s1f_desc.  q, out, dout, dq share the q_* strides; k, v share the
  *     kv_* strides; dk_prefix_acc, dv_prefix_acc share the kv_* strides too (in fp32 elements).
  *     lse is a dense fp32 array [batch, n_q_heads, seg_len].
  *   - Query head h reads key/value head h / (n_q_heads / n_kv_heads) (contiguous groups).
  *   - Kernels are enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default stream) and
- *     the call returns without synchronising.  Arguments are validated before anything is enqueued; on
- *     an error status nothing has been launched and no output was touched.
+ *     the call returns without synchronising.  Arguments are validated before anything is enqueued: on
+ *     S1F_EINVAL, S1F_EUNSUPPORTED or S1F_ERANGE nothing has been launched and no output was touched.
+ *     S1F_EDEVICE reports that the HIP runtime refused a launch of THIS call (errors left behind by the
+ *     caller's earlier HIP work are not picked up); a call made of several launches (s1f_seg_attn_bwd, the
+ *     cache calls with batch > 1) may then have enqueued its earlier ones, so its outputs are undefined.
  *   - Every entry point returns an s1f_status; nothing throws or aborts across this boundary.
  */
 #ifndef S1F_H

@@ -1,6 +1,7 @@
 // C ABI of the library: argument validation and kernel dispatch.  See include/s1f.h for the contract.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 
@@ -32,6 +33,7 @@ int check_desc(const s1f_desc *d) {
   if (d->dtype != S1F_F32 && d->dtype != S1F_BF16) return S1F_EUNSUPPORTED;
   if (d->head_dim != 64 && d->head_dim != 80 && d->head_dim != 128) return S1F_EUNSUPPORTED;
   if (d->batch > 65535 || d->n_q_heads > 65535) return S1F_EUNSUPPORTED;
+  if ((int64_t)d->batch * d->n_q_heads > 0x7fffffff) return S1F_EUNSUPPORTED;   // (batch, head) pairs are counted in 32 bits
   // 16-byte vector accesses: every row must start on a 16-byte boundary
   const int64_t ce = d->dtype == S1F_BF16 ? 8 : 4;
   const int64_t s[6] = {d->q_stride_b, d->q_stride_h, d->q_stride_s, d->kv_stride_b, d->kv_stride_h, d->kv_stride_s};
@@ -59,44 +61,66 @@ AttnArgs make_args(const s1f_desc *d, int64_t seg_off, int64_t seg_len) {
   return a;
 }
 
-// One-dimensional grid of n_tiles * n_bh workgroups; the kernels decode (tile, batch*head) themselves.
-// `tile_major`: order of the workgroups within an XCD; chosen per kernel from the shape of the segment.
-template <typename K>
-int launch(K kernel, int n_tiles, int n_bh, int tile_major, int threads, int lds_bytes, AttnArgs a, hipStream_t st) {
-  if ((int64_t)n_tiles * n_bh > 0x7fffffff) return S1F_EUNSUPPORTED;
-  a.n_tiles = n_tiles;
-  a.n_bh = n_bh;
-  a.tile_major = tile_major;
-  const dim3 grid((unsigned)((int64_t)n_tiles * n_bh));
-  if (lds_bytes > 64 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            lds_bytes) != hipSuccess)
-      return S1F_EDEVICE;
-  }
-  hipLaunchKernelGGL(kernel, grid, dim3(threads), lds_bytes, st, a);
-  return hipGetLastError() == hipSuccess ? S1F_OK : S1F_EDEVICE;
+// Kernels that need more than 64 KiB of LDS have to be told so once per device; `prepare` does that the first time
+// a kernel instantiation is used on the current device (a template: one flag set per instantiation).
+constexpr int kMaxDevices = 64;
+template <typename K> int prepare(K kernel, int lds_bytes) {
+  if (lds_bytes <= 64 * 1024) return S1F_OK;
+  static std::atomic<bool> done[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return S1F_EDEVICE;
+  const bool cached = dev >= 0 && dev < kMaxDevices;
+  if (cached && done[dev].load(std::memory_order_acquire)) return S1F_OK;
+  if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          lds_bytes) != hipSuccess)
+    return S1F_EDEVICE;
+  if (cached) done[dev].store(true, std::memory_order_release);
+  return S1F_OK;
 }
 
-template <typename T, int D> int fwd_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
+// One-dimensional grid of n_tiles * n_bh workgroups; the kernels decode (tile, batch*head) themselves.
+// `tile_major`: order of the workgroups within an XCD; chosen per kernel from the shape of the segment.
+// With `enqueue` false only the one-time preparation runs, so that a caller of several kernels can finish
+// everything that may fail before the first of them is enqueued.  The status reflects this launch only (the
+// return code of the launch call, not the runtime's sticky last error).
+template <typename K>
+int launch(K kernel, int64_t n_tiles, int64_t n_bh, int tile_major, int threads, int lds_bytes, AttnArgs a, hipStream_t st,
+           bool enqueue) {
+  if (n_tiles * n_bh > 0x7fffffff) return S1F_EUNSUPPORTED;
+  const int rc = prepare(kernel, lds_bytes);
+  if (rc != S1F_OK || !enqueue) return rc;
+  a.n_tiles = (int32_t)n_tiles;
+  a.n_bh = (int32_t)n_bh;
+  a.tile_major = tile_major;
+  void *params[] = {&a};
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)(n_tiles * n_bh)),
+                                       dim3(threads), params, (size_t)lds_bytes, st);
+  return e == hipSuccess ? S1F_OK : S1F_EDEVICE;
+}
+
+template <typename T, int D> int fwd_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
   typedef Shape<T> S;
   typedef FwdCfg<T, D, S::FNQ, S::FKB, S::FNW> Cfg;
   return launch(seg_attn_fwd_kernel<T, D, S::FNQ, S::FKB, S::FNW, S::FOCC>, (a.seg_len + Cfg::BM - 1) / Cfg::BM,
-                d->n_q_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, Cfg::THREADS, Cfg::LDS_BYTES, a, st);
+                (int64_t)d->n_q_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, Cfg::THREADS,
+                Cfg::LDS_BYTES, a, st, enqueue);
 }
 
-template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
+template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
   typedef Shape<T> S;
   typedef BwdDqCfg<T, D, S::QNQ, S::QBN> QC;
   return launch(seg_attn_bwd_dq_kernel<T, D, S::QNQ, S::QBN, S::QOCC>, (a.seg_len + QC::BM - 1) / QC::BM,
-                d->n_q_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, 256, QC::LDS_BYTES, a, st);
+                (int64_t)d->n_q_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, 256, QC::LDS_BYTES, a, st,
+                enqueue);
 }
 
-template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st) {
+template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
   typedef Shape<T> S;
   typedef BwdDkdvCfg<T, D, S::KNW, S::KDIST, S::KLAG> KC;
-  const int kv_len = a.seg_off + a.seg_len;
+  const int64_t kv_len = (int64_t)a.seg_off + a.seg_len;
   return launch(seg_attn_bwd_dkdv_kernel<T, D, S::KNW, S::KDIST, S::KLAG>, (kv_len + KC::BNW - 1) / KC::BNW,
-                d->n_kv_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, KC::THREADS, KC::LDS_BYTES, a, st);
+                (int64_t)d->n_kv_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, KC::THREADS, KC::LDS_BYTES,
+                a, st, enqueue);
 }
 
 
@@ -131,7 +155,7 @@ extern "C" int s1f_seg_attn_fwd(const s1f_desc *desc, const void *q_seg, const v
   AttnArgs a = make_args(desc, seg_off, seg_len);
   a.q = q_seg; a.k = k_prefix; a.v = v_prefix; a.out_w = out; a.lse = lse;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  S1F_DISPATCH(fwd_impl, desc, desc, a, st);
+  S1F_DISPATCH(fwd_impl, desc, desc, a, st, true);
 }
 
 extern "C" size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len) {
@@ -140,8 +164,12 @@ extern "C" size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off,
 }
 
 namespace {
-int bwd_dq_dispatch(const s1f_desc *d, const AttnArgs &a, hipStream_t st) { S1F_DISPATCH(bwd_dq_impl, d, d, a, st); }
-int bwd_dkdv_dispatch(const s1f_desc *d, const AttnArgs &a, hipStream_t st) { S1F_DISPATCH(bwd_dkdv_impl, d, d, a, st); }
+int bwd_dq_dispatch(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
+  S1F_DISPATCH(bwd_dq_impl, d, d, a, st, enqueue);
+}
+int bwd_dkdv_dispatch(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
+  S1F_DISPATCH(bwd_dkdv_impl, d, d, a, st, enqueue);
+}
 
 // Validation shared by the backward entry points; fills `a` on success.
 int bwd_prepare(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix, const void *v_prefix,
@@ -156,12 +184,13 @@ int bwd_prepare(const s1f_desc *desc, const void *dout, const void *q_seg, const
   if (rc != S1F_OK) return rc;
   if (workspace_bytes < s1f_bwd_workspace_bytes(desc, seg_off, seg_len)) return S1F_EINVAL;
   // the asynchronous copies address the workspace with 32-bit byte offsets
-  if (desc->batch * desc->n_q_heads * seg_len > (int64_t(1) << 28)) return S1F_EUNSUPPORTED;
+  const int64_t stat_rows = (int64_t)desc->batch * desc->n_q_heads * seg_len;
+  if (stat_rows > (int64_t(1) << 28)) return S1F_EUNSUPPORTED;
   *a = make_args(desc, seg_off, seg_len);
   a->q = q_seg; a->k = k_prefix; a->v = v_prefix; a->dout = dout;
   a->lse = const_cast<float *>(lse);
   a->delta = reinterpret_cast<float *>(const_cast<void *>(workspace));
-  a->ws_plane = desc->batch * desc->n_q_heads * seg_len;
+  a->ws_plane = stat_rows;
   return S1F_OK;
 }
 }  // namespace
@@ -175,7 +204,7 @@ extern "C" int s1f_seg_attn_bwd_dq(const s1f_desc *desc, const void *dout, const
   if (rc != S1F_OK) return rc;
   if (!out || !dq || !aligned16(out) || !aligned16(dq)) return S1F_EINVAL;
   a.out = out; a.dq = dq;
-  return bwd_dq_dispatch(desc, a, reinterpret_cast<hipStream_t>(hip_stream));
+  return bwd_dq_dispatch(desc, a, reinterpret_cast<hipStream_t>(hip_stream), true);
 }
 
 extern "C" int s1f_seg_attn_bwd_dkdv(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
@@ -187,7 +216,7 @@ extern "C" int s1f_seg_attn_bwd_dkdv(const s1f_desc *desc, const void *dout, con
   if (rc != S1F_OK) return rc;
   if (!dk_prefix_acc || !dv_prefix_acc || !aligned16(dk_prefix_acc) || !aligned16(dv_prefix_acc)) return S1F_EINVAL;
   a.dk_acc = dk_prefix_acc; a.dv_acc = dv_prefix_acc;
-  return bwd_dkdv_dispatch(desc, a, reinterpret_cast<hipStream_t>(hip_stream));
+  return bwd_dkdv_dispatch(desc, a, reinterpret_cast<hipStream_t>(hip_stream), true);
 }
 
 extern "C" int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
@@ -201,9 +230,13 @@ extern "C" int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const vo
   if (!aligned16(out) || !aligned16(dq) || !aligned16(dk_prefix_acc) || !aligned16(dv_prefix_acc)) return S1F_EINVAL;
   a.out = out; a.dq = dq; a.dk_acc = dk_prefix_acc; a.dv_acc = dv_prefix_acc;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  const int rq = bwd_dq_dispatch(desc, a, st);
-  if (rq != S1F_OK) return rq;
-  return bwd_dkdv_dispatch(desc, a, st);
+  // everything that can fail short of the launches themselves happens before the first kernel is enqueued
+  int rc2 = bwd_dq_dispatch(desc, a, st, false);
+  if (rc2 == S1F_OK) rc2 = bwd_dkdv_dispatch(desc, a, st, false);
+  if (rc2 != S1F_OK) return rc2;
+  rc2 = bwd_dq_dispatch(desc, a, st, true);
+  if (rc2 != S1F_OK) return rc2;
+  return bwd_dkdv_dispatch(desc, a, st, true);
 }
 
 extern "C" const char *s1f_strerror(int status) {

@@ -55,8 +55,11 @@ template <typename SRC, typename DST> int launch_rows(const CopyArgs &a, hipStre
   const int64_t total = (int64_t)a.heads * a.rows * a.chunks;
   const int64_t blocks = (total + 255) / 256;
   if (blocks > 0x7fffffff) return S1F_EUNSUPPORTED;
-  hipLaunchKernelGGL((rows_kernel<SRC, DST>), dim3((unsigned)blocks), dim3(256), 0, st, a);
-  return hipGetLastError() == hipSuccess ? S1F_OK : S1F_EDEVICE;
+  CopyArgs args = a;
+  void *params[] = {&args};
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&rows_kernel<SRC, DST>), dim3((unsigned)blocks),
+                                       dim3(256), params, 0, st);
+  return e == hipSuccess ? S1F_OK : S1F_EDEVICE;
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }

@@ -1,0 +1,153 @@
+"""GPU parity beyond one sequence and beyond hand-picked boundaries: several independent sequences in one set
+of calls (batch > 1), launches that take the XCD-aware workgroup order in both of its variants, prefix
+accumulation over many launches compared element by element, and a seeded random sweep over offsets,
+lengths, head dimensions, head groupings and layouts.  Tolerances are the contract's (see test_gpu_parity)."""
+import numpy as np
+import pytest
+
+import s1f_synth as S
+from oracle import attention as A
+from oracle import cache as C
+
+pytestmark = pytest.mark.gpu
+
+F32_MAXABS = 1e-4
+BF16_MAXABS, BF16_RELFRO = 2e-2, 1e-2
+LSE_MAXABS_BF16 = 1e-3
+
+
+def _check(res, want, dtype, where=""):
+    from gpu_harness import errors
+    for name in ("out", "lse", "dq", "dk", "dv"):
+        assert np.isfinite(res[name]).all(), f"{where}{name} has non-finite values"
+        mx, fro = errors(res[name], want[name])
+        if dtype == "f32":
+            assert mx <= F32_MAXABS, f"{where}{name}: max abs {mx}"
+        elif name == "lse":
+            assert mx <= LSE_MAXABS_BF16, f"{where}lse: max abs {mx}"
+        else:
+            assert mx <= BF16_MAXABS and fro <= BF16_RELFRO, f"{where}{name}: max abs {mx} rel fro {fro}"
+
+
+def _sequence(seed, hq, hkv, n, d, dtype):
+    return (S.tensor(seed, "q", hq, n, d, dtype), S.tensor(seed, "k", hkv, n, d, dtype),
+            S.tensor(seed, "v", hkv, n, d, dtype), S.tensor(seed, "dout", hq, n, d, dtype))
+
+
+def _oracle(q, k, v, do):
+    out, lse = A.full_forward(q, k, v)
+    dq, dk, dv = A.full_backward(do, q, k, v)
+    return {"out": out, "lse": lse, "dq": dq, "dk": dk, "dv": dv}
+
+
+# A short first segment (workgroups ordered tile by tile inside an XCD) followed by segments behind a prefix longer
+# than themselves (ordered head by head), with unaligned boundaries and a ragged tail.
+BOUNDS = [0, 300, 500, 1100, 1357]
+
+
+@pytest.mark.parametrize("dtype,d,layout", [("bf16", 128, "bhsd"), ("bf16", 80, "bshd"), ("f32", 64, "bshd"),
+                                            ("f32", 128, "bhsd")])
+@pytest.mark.parametrize("nb,hq,hkv", [(3, 8, 2), (2, 4, 4)])
+def test_several_sequences_in_one_call(dtype, d, layout, nb, hq, hkv):
+    """Every batch entry is a sequence of its own (distinct data) and must equal full causal attention on it.
+    3 x 8 query heads give 24 (batch, head) pairs: the forward and dQ kernels take the XCD-aware order; 2 x 4
+    K/V heads do the same for the dK/dV kernel.  The K/V rows travel through s1f_kv_append and the final
+    gradient rows through s1f_kv_grad_emit."""
+    from gpu_harness import run_schedule_batched
+    n = BOUNDS[-1]
+    seqs = [_sequence(300 + 17 * b + d, hq, hkv, n, d, dtype) for b in range(nb)]
+    q, k, v, do = (np.stack([s[i] for s in seqs]) for i in range(4))
+    fin = []
+    res = run_schedule_batched(q, k, v, do, BOUNDS, dtype, capacity=n + 40, layout=layout, finality=fin,
+                               cache_kernels=True)
+    assert (res["dk"][:, :, n:] == 777.0).all() and (res["dv"][:, :, n:] == 777.0).all()
+    assert np.array_equal(res["k_cache"][:, :, :n], k) and np.array_equal(res["v_cache"][:, :, :n], v)
+    for b in range(nb):
+        want = _oracle(*seqs[b])
+        got = {name: res[name][b][:, :n] if name in ("dk", "dv") else res[name][b] for name in want}
+        _check(got, want, dtype, where=f"batch entry {b}: ")
+    # emitted rows are the accumulators' rows at the moment of the emit, converted bit-exactly
+    for i, dk_i, dv_i in fin:
+        a, e = BOUNDS[i], BOUNDS[i + 1]
+        for b in range(nb):
+            wk, wv = C.kv_grad_emit(dk_i[b], dv_i[b], a, e - a, dtype)
+            assert np.array_equal(res["dk_emit"][b][:, a:e], wk) and np.array_equal(res["dv_emit"][b][:, a:e], wv)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_eight_heads_both_workgroup_orders(dtype):
+    """One sequence, 8 query heads on 8 K/V heads: all three kernels take the XCD-aware order, tile-major for the
+    first segment and head-major behind the long prefix; compared element by element."""
+    from gpu_harness import run_schedule
+    q, k, v, do = _sequence(911, 8, 8, BOUNDS[-1], 128, dtype)
+    _check(run_schedule(q, k, v, do, BOUNDS, dtype), _oracle(q, k, v, do), dtype)
+
+
+@pytest.mark.parametrize("n_seg,hq,hkv,hidden", [(32, 64, 8, 8192), (16, 56, 56, 7168)])
+def test_prefix_accumulation_over_every_launch(n_seg, hq, hkv, hidden):
+    """16384 tokens in 32 (16) equal-cost segments with the head structure of the two largest workloads, driven by
+    the same Stage object the benchmark times.  The keys of the FIRST segment receive a += from every one of the 32
+    (16) backward launches; their dK/dV are compared element by element with the row oracle, as are keys at later
+    boundaries and the outputs and dQ of rows spread over the sequence."""
+    import torch
+    import bench
+    import paper_2406_03488_amd as s1f
+    from gpu_harness import errors
+    from oracle import rows
+
+    n, d = 16384, 128
+    w = S.Workload(f"acc{n_seg}", n, n_seg, hq, hkv, d, hidden, "bf16", "cwp", 20240700 + n_seg)
+    stage = bench.Stage(w, torch, s1f)
+    bounds = stage.step()
+    torch.cuda.synchronize()
+    assert len(bounds) == n_seg + 1
+    grp = hq // hkv
+    g = hkv - 3
+    heads = list(range(g * grp, (g + 1) * grp))
+    q = stage.q[0, heads].float().cpu().numpy(); do = stage.dout[0, heads].float().cpu().numpy()
+    k = stage.k[0, g:g + 1].float().cpu().numpy(); v = stage.v[0, g:g + 1].float().cpu().numpy()
+    key_sets = [(0, 24), (bounds[1] - 12, bounds[1] + 12), (bounds[n_seg // 2] - 8, bounds[n_seg // 2] + 8), (n - 24, n)]
+    for j0, j1 in key_sets:
+        print(f"  keys {j0}..{j1} of kv head {g}", flush=True)
+        dk_ref, dv_ref = rows.dkdv_keys(q, k, v, do, 0, j0, j1)
+        for name, got, ref in (("dk", stage.dk, dk_ref), ("dv", stage.dv, dv_ref)):
+            mx, fro = errors(got[0, g, j0:j1].cpu().numpy(), ref)
+            assert mx <= BF16_MAXABS and fro <= BF16_RELFRO, (name, j0, mx, fro)
+    hl = grp - 1
+    for r0, r1 in [(0, 16), (bounds[1] - 8, bounds[1] + 8), (bounds[-2] - 8, bounds[-2] + 8), (n - 16, n)]:
+        o_ref, _ = rows.forward_rows(q, k, v, hl, r0, r1)
+        dq_ref = rows.dq_rows(q, k, v, do, hl, r0, r1)
+        for name, got, ref in (("out", stage.out, o_ref), ("dq", stage.dq, dq_ref)):
+            mx, fro = errors(got[0, heads[hl], r0:r1].float().cpu().numpy(), ref)
+            assert mx <= BF16_MAXABS and fro <= BF16_RELFRO, (name, r0, mx, fro)
+
+
+def _sweep_cases(count, seed):
+    """(seg_off, seg_len, head_dim, Hq, Hkv, dtype, layout): lengths of one to three row tiles (128 rows) plus or
+    minus a token and a few tiny ones, offsets from 0 to a few key tiles (aligned and not)."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    lens = [1, 2, 31, 33, 127, 128, 129, 255, 256, 257, 383, 384, 385]
+    offs = [0, 0, 1, 31, 32, 63, 64, 65, 127, 128, 255, 256, 257, 300, 511, 512, 640, 777]
+    groups = [(1, 1), (2, 1), (2, 2), (4, 2), (3, 3), (8, 2), (6, 1)]
+    cases = []
+    for _ in range(count):
+        hq, hkv = groups[rng.integers(len(groups))]
+        cases.append((int(offs[rng.integers(len(offs))]), int(lens[rng.integers(len(lens))]),
+                      int((64, 80, 128)[rng.integers(3)]), hq, hkv, ("f32", "bf16")[rng.integers(2)],
+                      ("bhsd", "bshd")[rng.integers(2)]))
+    return cases
+
+
+def test_random_sweep_single_segment_calls():
+    """64 seeded random single-segment calls (forward + backward at an arbitrary offset) against the oracle's
+    segment-wise definition; stops at the first failure and names the case."""
+    from gpu_harness import run_segment
+    for idx, (off, m, d, hq, hkv, dtype, layout) in enumerate(_sweep_cases(64, 20240611)):
+        case = f"case {idx}: seg_off={off} seg_len={m} D={d} heads={hq}/{hkv} {dtype} {layout}: "
+        print(case, flush=True)
+        n = off + m
+        q, k, v, do = _sequence(5000 + idx, hq, hkv, n, d, dtype)
+        res = run_segment(q[:, off:], k, v, do[:, off:], off, dtype, layout)
+        out, lse = A.segment_forward(q[:, off:], k, v, off)
+        dq, dk, dv = A.segment_backward(do[:, off:], q[:, off:], k, v, off)
+        _check(res, {"out": out, "lse": lse, "dq": dq, "dk": dk, "dv": dv}, dtype, where=case)

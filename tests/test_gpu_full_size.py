@@ -19,7 +19,8 @@ def _errors(got, want):
 
 
 @pytest.mark.parametrize("name,second_keys", [("2.7b", "first-boundary"), ("7b", "first-boundary"),
-                                              ("30b", "last-boundary"), ("gqa", "late")])
+                                              ("30b", "last-boundary"), ("30b-uniform", "last-boundary"),
+                                              ("gqa", "late")])
 def test_full_size_workload_sampled_against_row_oracle(name, second_keys):
     import torch
     import bench

@@ -177,6 +177,8 @@ def test_attention_entry_points_validate_before_any_launch():
     assert fwd(_desc(dtype=7)) == 2
     assert fwd(_desc(kv_stride_s=1 << 23, kv_stride_h=1 << 40, kv_stride_b=1 << 41)) == 2   # row stride beyond the kernels' reach
     assert fwd(_desc(q_stride_s=1 << 23, q_stride_h=1 << 40, q_stride_b=1 << 41)) == 2
+    # more (batch, head) pairs than the kernels' 32-bit counters hold; 65535 x 40000 would wrap a 32-bit product
+    assert fwd(_desc(batch=65535, n_q_heads=40000, n_kv_heads=40000)) == 2
     assert fwd(_desc(), seg_off=-1) == 3
     assert fwd(_desc(), seg_len=0) == 3
     assert fwd(_desc(), seg_off=300, seg_len=256) == 3            # past kv_capacity
@@ -189,6 +191,10 @@ def test_attention_entry_points_validate_before_any_launch():
     assert bwd(_desc(), ws_bytes=4 * 256 * 4 - 1) == 1
     assert bwd(_desc(), seg_off=400, seg_len=200) == 3
     assert bwd(_desc(head_dim=32)) == 2
+    # batch * heads * seg_len beyond the workspace's 32-bit offsets: 4096 * 4096 * 17 rows of statistics (the
+    # product of the first two wraps to 2^24 in 32 bits and must not slip through as a small number)
+    big = _desc(batch=4096, n_q_heads=4096, n_kv_heads=4096)
+    assert bwd(big, seg_len=17, ws_bytes=1 << 62) == 2
     assert lib.s1f_bwd_workspace_bytes(ctypes.byref(_desc()), 0, 256) == 2 * 4 * 256 * 4
     assert lib.s1f_bwd_workspace_bytes(ctypes.byref(_desc()), 500, 256) == 0
     for code in range(0, 6):
