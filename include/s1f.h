@@ -44,7 +44,8 @@ typedef enum {
   S1F_EINVAL = 1,       /* null pointer, non-positive size, inconsistent descriptor */
   S1F_EUNSUPPORTED = 2, /* dtype / head_dim combination without a kernel, or a size beyond a kernel's limits */
   S1F_ERANGE = 3,       /* segment does not fit: seg_off < 0, seg_len < 1, seg_off + seg_len > kv_capacity */
-  S1F_EDEVICE = 4       /* the HIP runtime reported an error at launch */
+  S1F_EDEVICE = 4,      /* the HIP runtime reported an error at launch */
+  S1F_ESCRATCH = 5      /* s1f_seg_attn_bwd_noalloc only: the call needs more scratch than the built-in buffer holds */
 } s1f_status;
 
 typedef enum {
@@ -160,6 +161,23 @@ int s1f_seg_attn_bwd_dkdv(const s1f_desc *desc, const void *dout, const void *q_
 
 /* Bytes of device scratch s1f_seg_attn_bwd needs for this call shape (0 on invalid arguments). */
 size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len);
+
+/* s1f_seg_attn_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments (without the
+ * workspace), same kernels and bit-identical results; the row statistics go to a device array built into the
+ * library (16 MiB per GPU, held until the process ends) instead of a caller-owned workspace.  The call
+ * allocates nothing and frees nothing.
+ *   Limit: batch * n_q_heads * seg_len <= s1f_static_scratch_rows() (2^21); beyond it the call returns
+ *   S1F_ESCRATCH before anything is launched.
+ *   Every call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU (different
+ *   streams or threads) race; calls on one stream, or ordered by events, do not.  Nothing in the array has to
+ *   start at zero and nothing in it is meaningful after the call.
+ * The first call on a device looks up the array's device address (no allocation). */
+int s1f_seg_attn_bwd_noalloc(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
+                             const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
+                             int64_t seg_len, void *dq, float *dk_prefix_acc, float *dv_prefix_acc,
+                             void *hip_stream);
+size_t s1f_static_scratch_rows(void);
 
 /* The two data movements on either side of a segment's attention calls (Section 3.2: the keys and values of
  * all preceding tokens are retained; gradients of earlier tokens are accumulated until the backward passes

@@ -73,6 +73,10 @@ def load_library():
     lib.s1f_seg_attn_bwd_dq.restype = ctypes.c_int
     lib.s1f_seg_attn_bwd_dkdv.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, sz, vp]
     lib.s1f_seg_attn_bwd_dkdv.restype = ctypes.c_int
+    lib.s1f_seg_attn_bwd_noalloc.argtypes = [dp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp]
+    lib.s1f_seg_attn_bwd_noalloc.restype = ctypes.c_int
+    lib.s1f_static_scratch_rows.argtypes = []
+    lib.s1f_static_scratch_rows.restype = sz
     lib.s1f_bwd_workspace_bytes.argtypes = [dp, i64, i64]
     lib.s1f_bwd_workspace_bytes.restype = sz
     lib.s1f_kv_append.argtypes = [dp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp]
@@ -265,6 +269,30 @@ def bwd_workspace_bytes(q_seg, k_prefix, seg_off: int) -> int:
     return int(load_library().s1f_bwd_workspace_bytes(ctypes.byref(desc), int(seg_off), int(q_seg.shape[2])))
 
 
+def _check_lse(lse, q_seg):
+    import torch
+    if lse.dtype != torch.float32:
+        raise TypeError("lse is fp32")
+    if not lse.is_contiguous() or lse.shape != q_seg.shape[:3]:
+        raise ValueError("lse must be a contiguous [B, Hq, seg_len] fp32 tensor")
+
+
+def _check_acc(k_prefix, v_prefix, dk_prefix_acc, dv_prefix_acc):
+    import torch
+    _same_layout(k_prefix, v_prefix)
+    _same_layout(dk_prefix_acc, dv_prefix_acc)
+    if dk_prefix_acc.shape != k_prefix.shape or dk_prefix_acc.stride() != k_prefix.stride():
+        raise ValueError("gradient accumulators must have the shape and strides of k_prefix")
+    if dk_prefix_acc.dtype != torch.float32:
+        raise TypeError("accumulators are fp32")
+
+
+def _check_bwd_tensors(dout, q_seg, k_prefix, v_prefix, out, lse, dq, dk_prefix_acc, dv_prefix_acc):
+    _same_layout(q_seg, dout, out, dq)
+    _check_acc(k_prefix, v_prefix, dk_prefix_acc, dv_prefix_acc)
+    _check_lse(lse, q_seg)
+
+
 def seg_attn_bwd(dout, q_seg, k_prefix, v_prefix, out, lse, seg_off: int, dq, dk_prefix_acc, dv_prefix_acc, workspace):
     """s1f_seg_attn_bwd on torch device tensors.
 
@@ -272,16 +300,7 @@ def seg_attn_bwd(dout, q_seg, k_prefix, v_prefix, out, lse, seg_off: int, dq, dk
     device tensor of at least bwd_workspace_bytes(...) bytes.
     """
     lib = load_library()
-    _same_layout(q_seg, dout, out, dq)
-    _same_layout(k_prefix, v_prefix)
-    _same_layout(dk_prefix_acc, dv_prefix_acc)
-    if dk_prefix_acc.shape != k_prefix.shape or dk_prefix_acc.stride() != k_prefix.stride():
-        raise ValueError("gradient accumulators must have the shape and strides of k_prefix")
-    import torch
-    if dk_prefix_acc.dtype != torch.float32 or lse.dtype != torch.float32:
-        raise TypeError("accumulators and lse are fp32")
-    if not lse.is_contiguous() or lse.shape != q_seg.shape[:3]:
-        raise ValueError("lse must be a contiguous [B, Hq, seg_len] fp32 tensor")
+    _check_bwd_tensors(dout, q_seg, k_prefix, v_prefix, out, lse, dq, dk_prefix_acc, dv_prefix_acc)
     desc = make_desc(q_seg, k_prefix)
     rc = lib.s1f_seg_attn_bwd(ctypes.byref(desc), dout.data_ptr(), q_seg.data_ptr(), k_prefix.data_ptr(),
                               v_prefix.data_ptr(), out.data_ptr(), lse.data_ptr(), int(seg_off), int(q_seg.shape[2]),
@@ -291,11 +310,29 @@ def seg_attn_bwd(dout, q_seg, k_prefix, v_prefix, out, lse, seg_off: int, dq, dk
         raise S1FError(rc, "s1f_seg_attn_bwd")
 
 
+def static_scratch_rows() -> int:
+    return int(load_library().s1f_static_scratch_rows())
+
+
+def seg_attn_bwd_noalloc(dout, q_seg, k_prefix, v_prefix, out, lse, seg_off: int, dq, dk_prefix_acc, dv_prefix_acc):
+    """s1f_seg_attn_bwd_noalloc on torch device tensors: s1f_seg_attn_bwd without a workspace argument."""
+    lib = load_library()
+    _check_bwd_tensors(dout, q_seg, k_prefix, v_prefix, out, lse, dq, dk_prefix_acc, dv_prefix_acc)
+    desc = make_desc(q_seg, k_prefix)
+    rc = lib.s1f_seg_attn_bwd_noalloc(ctypes.byref(desc), dout.data_ptr(), q_seg.data_ptr(), k_prefix.data_ptr(),
+                                      v_prefix.data_ptr(), out.data_ptr(), lse.data_ptr(), int(seg_off),
+                                      int(q_seg.shape[2]), dq.data_ptr(), dk_prefix_acc.data_ptr(),
+                                      dv_prefix_acc.data_ptr(), _stream_ptr())
+    if rc != 0:
+        raise S1FError(rc, "s1f_seg_attn_bwd_noalloc")
+
+
 def seg_attn_bwd_dq(dout, q_seg, k_prefix, v_prefix, out, lse, seg_off: int, dq, workspace):
     """s1f_seg_attn_bwd_dq: first half of the backward (dq, and delta into the workspace)."""
     lib = load_library()
     _same_layout(q_seg, dout, out, dq)
     _same_layout(k_prefix, v_prefix)
+    _check_lse(lse, q_seg)
     desc = make_desc(q_seg, k_prefix)
     rc = lib.s1f_seg_attn_bwd_dq(ctypes.byref(desc), dout.data_ptr(), q_seg.data_ptr(), k_prefix.data_ptr(),
                                  v_prefix.data_ptr(), out.data_ptr(), lse.data_ptr(), int(seg_off),
@@ -309,10 +346,8 @@ def seg_attn_bwd_dkdv(dout, q_seg, k_prefix, v_prefix, lse, seg_off: int, dk_pre
     """s1f_seg_attn_bwd_dkdv: second half of the backward (prefix dK/dV accumulation)."""
     lib = load_library()
     _same_layout(q_seg, dout)
-    _same_layout(k_prefix, v_prefix)
-    _same_layout(dk_prefix_acc, dv_prefix_acc)
-    if dk_prefix_acc.shape != k_prefix.shape or dk_prefix_acc.stride() != k_prefix.stride():
-        raise ValueError("gradient accumulators must have the shape and strides of k_prefix")
+    _check_acc(k_prefix, v_prefix, dk_prefix_acc, dv_prefix_acc)
+    _check_lse(lse, q_seg)
     desc = make_desc(q_seg, k_prefix)
     rc = lib.s1f_seg_attn_bwd_dkdv(ctypes.byref(desc), dout.data_ptr(), q_seg.data_ptr(), k_prefix.data_ptr(),
                                    v_prefix.data_ptr(), lse.data_ptr(), int(seg_off), int(q_seg.shape[2]),

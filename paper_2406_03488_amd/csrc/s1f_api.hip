@@ -4,6 +4,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 
 #include "attn_bwd.hpp"
 #include "attn_fwd.hpp"
@@ -239,6 +240,50 @@ extern "C" int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const vo
   return bwd_dkdv_dispatch(desc, a, st, true);
 }
 
+// ---- the backward for callers that cannot allocate --------------------------------------------------------------
+// Its row statistics live in a device array that is part of the library's code object instead of a workspace
+// argument.  In host code the array's name is only a handle: its device address is looked up once per device
+// (each device holds its own copy) and that address is what the kernels receive.
+namespace {
+constexpr int64_t kStaticStatRows = int64_t(1) << 21;            // batch * n_q_heads * seg_len the array holds
+static __device__ __align__(256) float scratch[2 * kStaticStatRows];   // two planes, 16 MiB per device
+
+std::mutex scratch_mutex;
+float *scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, null until looked up
+
+int static_scratch(float **out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return S1F_EDEVICE;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (scratch_ptr[dev] == nullptr) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return S1F_EDEVICE;
+    scratch_ptr[dev] = static_cast<float *>(p);
+  }
+  *out = scratch_ptr[dev];
+  return S1F_OK;
+}
+}  // namespace
+
+extern "C" size_t s1f_static_scratch_rows(void) { return (size_t)kStaticStatRows; }
+
+extern "C" int s1f_seg_attn_bwd_noalloc(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix,
+                                        const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
+                                        int64_t seg_len, void *dq, float *dk_prefix_acc, float *dv_prefix_acc,
+                                        void *hip_stream) {
+  int rc = check_desc(desc);
+  if (rc != S1F_OK) return rc;
+  rc = check_seg(desc, seg_off, seg_len);
+  if (rc != S1F_OK) return rc;
+  if ((int64_t)desc->batch * desc->n_q_heads * seg_len > kStaticStatRows) return S1F_ESCRATCH;
+  float *ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != S1F_OK) return rc;
+  // every plane entry the dK/dV kernel reads is written by the dQ kernel of the same call: nothing to clear
+  return s1f_seg_attn_bwd(desc, dout, q_seg, k_prefix, v_prefix, out, lse, seg_off, seg_len, dq, dk_prefix_acc,
+                          dv_prefix_acc, ws, 2 * (size_t)kStaticStatRows * sizeof(float), hip_stream);
+}
+
 extern "C" const char *s1f_strerror(int status) {
   switch (status) {
     case S1F_OK: return "ok";
@@ -246,8 +291,11 @@ extern "C" const char *s1f_strerror(int status) {
     case S1F_EUNSUPPORTED: return "unsupported dtype or head_dim (supported: f32/bf16 with head_dim 64, 80, 128)";
     case S1F_ERANGE: return "segment out of range (seg_off < 0, seg_len < 1 or seg_off + seg_len > kv_capacity)";
     case S1F_EDEVICE: return "HIP runtime error at kernel launch";
+    case S1F_ESCRATCH:
+      return "batch * n_q_heads * seg_len exceeds the built-in scratch of s1f_seg_attn_bwd_noalloc "
+             "(s1f_static_scratch_rows); use s1f_seg_attn_bwd with a workspace";
     default: return "unknown status";
   }
 }
 
-extern "C" int s1f_version(void) { return 100; }
+extern "C" int s1f_version(void) { return 200; }

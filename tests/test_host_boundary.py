@@ -201,6 +201,20 @@ def test_attention_entry_points_validate_before_any_launch():
         assert isinstance(s1f.strerror(code), str) and s1f.strerror(code)
 
 
+def test_noalloc_backward_rejects_more_rows_than_the_array_holds():
+    lib = s1f.load_library()
+    rows = s1f.static_scratch_rows()
+    assert rows == 1 << 21
+    p = ctypes.c_void_p(4096)       # never dereferenced: the size check comes before any launch
+    hq = 64
+    m = rows // hq + 1
+    desc = binding.Desc(batch=1, n_q_heads=hq, n_kv_heads=8, head_dim=128, dtype=1, reserved=0, q_stride_b=hq * m * 128,
+                        q_stride_h=m * 128, q_stride_s=128, kv_stride_b=8 * m * 128, kv_stride_h=m * 128,
+                        kv_stride_s=128, kv_capacity=m)
+    rc = lib.s1f_seg_attn_bwd_noalloc(ctypes.byref(desc), p, p, p, p, p, p, 0, m, p, p, p, None)
+    assert rc == 5 and "scratch" in s1f.strerror(rc)
+
+
 def test_seq1f1b_order_matches_oracle():
     """The library enumerates the order in closed form; the oracle simulates the queue of Section 3.2."""
     from oracle import schedule as SCH
