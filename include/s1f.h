@@ -224,6 +224,14 @@ int s1f_seq1f1b_warmup(int32_t pp_size, int32_t device, int32_t n_micro, int32_t
 int s1f_seq1f1b_order(int32_t pp_size, int32_t device, int32_t n_micro, int32_t n_seg, s1f_pass *order,
                       int64_t capacity, int64_t *n_passes);
 
+/* Peak activation memory of one device (Section 3.1): with A the memory of all intermediate states of a batch,
+ * device i holds A * w_i / sum_j w_j at its peak, w the warm-up counts (Eq. 1 for n_seg = 1, Eq. 4 otherwise).
+ * Writes the exact fraction: *numerator = w_i, *denominator = sum over the P devices of w_j (not reduced).  HOST
+ * function.  Errors: S1F_EINVAL as for s1f_seq1f1b_warmup, a NULL result pointer, or a zero sum (one device running
+ * whole sequences has no warm-up phase; the formula is undefined there). */
+int s1f_seq1f1b_peak_memory_share(int32_t pp_size, int32_t device, int32_t n_micro, int32_t n_seg,
+                                  int64_t *numerator, int64_t *denominator);
+
 /* Interleaved sequence-level schedule (Section 3.3): device i owns the n_chunks stages i, i + P, ..., and
  * switches to its next stage after P passes.  HOST functions, no device work.
  *
@@ -236,7 +244,9 @@ int s1f_seq1f1b_order(int32_t pp_size, int32_t device, int32_t n_micro, int32_t 
  * inside a group the tail segment of the earliest micro-batch first (Section 3.2's queue); warm-up forward passes,
  * then one forward and one backward per step, then the remaining backward passes.
  * Errors: S1F_EINVAL as for s1f_seq1f1b_order or n_chunks < 1; S1F_EUNSUPPORTED unless a group holds whole
- * micro-batches (k divides P) and P divides M * k. */
+ * micro-batches (k divides P) and P divides M * k.  That restriction belongs to this reading, not to the paper:
+ * the text fixes the order only through a figure for k = 4 on P = 4 devices with two stages each, which the
+ * reading reproduces; for other shapes the paper gives nothing to decide between the possible group layouts. */
 typedef struct {
   int32_t kind;        /* 0 = forward pass, 1 = backward pass */
   int32_t micro_batch; /* 0-based */
@@ -263,7 +273,8 @@ int s1f_seq1f1b_interleaved_order(int32_t pp_size, int32_t device, int32_t n_mic
  * A sub-sequence's states count as held from its forward pass to its backward pass (to its weight-gradient pass
  * when split).
  * Results (caller-owned HOST memory): *makespan; busy[P]; peak_live[P] in units of seg_tokens (sub-sequences when
- * seg_tokens is NULL); peak_pending_wgrad[P] (may be NULL).
+ * seg_tokens is NULL); peak_pending_wgrad[P] (may be NULL); *bubble_ratio = 1 - sum(busy) / (P * makespan), 0 for an
+ * empty timeline (may be NULL).
  * Errors: S1F_EINVAL for null pointers, counts < 1, negative or > 2^36 times, reserved != 0, or
  * M * k * n_chunks * P > 2^24; S1F_EUNSUPPORTED where s1f_seq1f1b_interleaved_order returns it. */
 typedef struct {
@@ -278,7 +289,7 @@ typedef struct {
   const int64_t *seg_tokens; /* [n_seg] weights of the held states, or NULL for 1 each */
 } s1f_pipeline_desc;
 int s1f_pipeline_simulate(const s1f_pipeline_desc *desc, int64_t *makespan, int64_t *busy, int64_t *peak_live,
-                          int64_t *peak_pending_wgrad);
+                          int64_t *peak_pending_wgrad, double *bubble_ratio);
 
 /* Static, NUL-terminated description of a status code. */
 const char *s1f_strerror(int status);

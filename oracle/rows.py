@@ -1,7 +1,7 @@
 """ctypes front end of oracle/attn_rows.c (row-by-row fp64 attention oracle).
 
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).  `build()` compiles the C file with gcc into
-oracle/_build/; the functions below marshal numpy arrays and return fp64 results.
+oracle/liboracle_rows.so (beside its source); the functions below marshal numpy arrays and return fp64 results.
 """
 from __future__ import annotations
 

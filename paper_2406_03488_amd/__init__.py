@@ -8,12 +8,12 @@ compute entry points raises.
 from .binding import (COST_ADDITIVE, COST_LITERAL, Desc, S1FError, bwd_workspace_bytes, kv_append, kv_grad_emit,
                       library_path, load_library, partition, partition_ex, partition_rebalance, pipeline_simulate,
                       seq1f1b_interleaved_order, seq1f1b_interleaved_warmup, seg_attn_bwd, seg_attn_bwd_dkdv, seg_attn_bwd_dq,
-                      seg_attn_bwd_noalloc, seg_attn_fwd, seq1f1b_order, static_scratch_rows,
+                      seg_attn_bwd_noalloc, seg_attn_fwd, seq1f1b_order, seq1f1b_peak_memory_share, static_scratch_rows,
                       seq1f1b_warmup, strerror, version)
 
 __all__ = ["COST_ADDITIVE", "COST_LITERAL", "Desc", "S1FError", "bwd_workspace_bytes", "kv_append", "kv_grad_emit",
            "library_path", "load_library", "partition", "partition_ex", "partition_rebalance", "pipeline_simulate",
            "seq1f1b_interleaved_order", "seq1f1b_interleaved_warmup",
            "seg_attn_bwd", "seg_attn_bwd_dkdv", "seg_attn_bwd_dq", "seg_attn_bwd_noalloc", "seg_attn_fwd",
-           "static_scratch_rows", "seq1f1b_order", "seq1f1b_warmup",
+           "static_scratch_rows", "seq1f1b_order", "seq1f1b_peak_memory_share", "seq1f1b_warmup",
            "strerror", "version"]

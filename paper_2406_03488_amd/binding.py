@@ -92,8 +92,10 @@ def load_library():
     lib.s1f_seq1f1b_interleaved_order.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(StagePass), i64,
                                                   ctypes.POINTER(i64)]
     lib.s1f_seq1f1b_interleaved_order.restype = ctypes.c_int
+    lib.s1f_seq1f1b_peak_memory_share.argtypes = [i32, i32, i32, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.s1f_seq1f1b_peak_memory_share.restype = ctypes.c_int
     lib.s1f_pipeline_simulate.argtypes = [ctypes.POINTER(PipelineDesc), ctypes.POINTER(i64), ctypes.POINTER(i64),
-                                          ctypes.POINTER(i64), ctypes.POINTER(i64)]
+                                          ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
     lib.s1f_pipeline_simulate.restype = ctypes.c_int
     lib.s1f_strerror.argtypes = [ctypes.c_int]
     lib.s1f_strerror.restype = ctypes.c_char_p
@@ -157,6 +159,16 @@ def seq1f1b_warmup(pp_size: int, device: int, n_micro: int, n_seg: int) -> int:
     return int(w.value)
 
 
+def seq1f1b_peak_memory_share(pp_size: int, device: int, n_micro: int, n_seg: int):
+    """s1f_seq1f1b_peak_memory_share: (numerator, denominator) of w_i / sum_j w_j."""
+    num, den = ctypes.c_int64(0), ctypes.c_int64(0)
+    rc = load_library().s1f_seq1f1b_peak_memory_share(int(pp_size), int(device), int(n_micro), int(n_seg),
+                                                      ctypes.byref(num), ctypes.byref(den))
+    if rc != 0:
+        raise S1FError(rc, "s1f_seq1f1b_peak_memory_share")
+    return int(num.value), int(den.value)
+
+
 def seq1f1b_order(pp_size: int, device: int, n_micro: int, n_seg: int):
     """s1f_seq1f1b_order: list of ("F" | "B", micro_batch, segment) in execution order."""
     lib = load_library()
@@ -194,8 +206,8 @@ def seq1f1b_interleaved_order(pp_size: int, device: int, n_micro: int, n_seg: in
 
 def pipeline_simulate(pp_size: int, n_micro: int, n_seg: int, n_chunks: int, t_fwd, t_bwd, t_wgrad=None,
                       t_comm: int = 0, max_pending_wgrad: int = 0, seg_tokens=None):
-    """s1f_pipeline_simulate: dict with makespan, busy, peak_live, peak_pending (lists over devices) and the
-    bubble ratio 1 - sum(busy) / (P * makespan) derived from them."""
+    """s1f_pipeline_simulate: dict with makespan, busy, peak_live, peak_pending (lists over devices) and
+    bubble_ratio, all as the library returns them."""
     k, P = int(n_seg), int(pp_size)
     if k < 1 or P < 1 or len(t_fwd) != k or len(t_bwd) != k or (t_wgrad is not None and len(t_wgrad) != k) or (
             seg_tokens is not None and len(seg_tokens) != k):
@@ -207,12 +219,13 @@ def pipeline_simulate(pp_size: int, n_micro: int, n_seg: int, n_chunks: int, t_f
                         int(t_comm), keep[0], keep[1], keep[2], keep[3])
     span = ctypes.c_int64(0)
     busy, live, pend = ((ctypes.c_int64 * P)() for _ in range(3))
-    rc = load_library().s1f_pipeline_simulate(ctypes.byref(desc), ctypes.byref(span), busy, live, pend)
+    bubble = ctypes.c_double(0.0)
+    rc = load_library().s1f_pipeline_simulate(ctypes.byref(desc), ctypes.byref(span), busy, live, pend,
+                                              ctypes.byref(bubble))
     if rc != 0:
         raise S1FError(rc, "s1f_pipeline_simulate")
-    out = {"makespan": int(span.value), "busy": list(busy), "peak_live": list(live), "peak_pending": list(pend)}
-    out["bubble_ratio"] = 1.0 - sum(out["busy"]) / (P * out["makespan"]) if out["makespan"] > 0 else 0.0
-    return out
+    return {"makespan": int(span.value), "busy": list(busy), "peak_live": list(live), "peak_pending": list(pend),
+            "bubble_ratio": float(bubble.value)}
 
 
 def _dtype_code(t):

@@ -13,12 +13,6 @@
 #pragma once
 #include "attn_device.hpp"
 
-// Optional cycle tracing of one wave (development aid, compiled out unless S1F_TRACE is defined).
-#ifdef S1F_TRACE
-#define S1F_BWD_MARK(slot) do { if (trace_on) trace_t[slot] = __builtin_readcyclecounter(); } while (0)
-#else
-#define S1F_BWD_MARK(slot) do { } while (0)
-#endif
 
 namespace s1f {
 

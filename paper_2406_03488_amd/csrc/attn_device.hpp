@@ -484,10 +484,6 @@ struct AttnArgs {
   int32_t n_tiles, n_bh;                 // launch shape: tiles per (batch, head) and number of (batch, head) pairs
   int32_t tile_major;                    // order of the workgroups within an XCD (see decode_workgroup)
   float scale;                           // 1/sqrt(head_dim)
-#ifdef S1F_TRACE
-  unsigned long long *trace;             // development aid: cycle stamps of one wave
-  unsigned trace_wg, trace_tid;
-#endif
 };
 
 }  // namespace s1f

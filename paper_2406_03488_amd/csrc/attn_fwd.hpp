@@ -17,12 +17,6 @@
 #pragma once
 #include "attn_device.hpp"
 
-// Optional cycle tracing of one wave (development aid, compiled out unless S1F_TRACE is defined).
-#ifdef S1F_TRACE
-#define S1F_TRACE_MARK(slot) do { if (trace_on) trace_t[slot] = __builtin_readcyclecounter(); } while (0)
-#else
-#define S1F_TRACE_MARK(slot) do { } while (0)
-#endif
 
 namespace s1f {
 
@@ -94,9 +88,6 @@ template <typename RD, typename T, bool HAS_NEXT, int NQ, int NKS, int DB>
 S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], const float (&m)[NQ], float (&l)[NQ],
                       float (&mx)[NQ], const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd,
                       lds_addr kblock_next, lds_addr vblock, float c, bool mask_next, int lim0_next
-#ifdef S1F_TRACE
-                      , bool trace_on, unsigned long long (&trace_t)[8]
-#endif
                       ) {
   typedef typename Elem<T>::Frag Frag;
   constexpr int NSLAB = 16 / Elem<T>::EPL;
@@ -151,7 +142,6 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
   }
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) l[nq] += rs[nq];
-  S1F_TRACE_MARK(2);
   // Blocks that cross the diagonal of this wave's rows get their mask here, in a branch of its own that holds
   // no matrix instruction: two instances of the whole step (with and without mask code) in one loop body make
   // the compiler keep the output accumulators in two places and copy all 64 registers on every step.
@@ -187,7 +177,6 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
       __builtin_amdgcn_sched_barrier(0);
     }
   }
-  S1F_TRACE_MARK(3);
   if (HAS_NEXT) {
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) mx[nq] = max_xor32(mxv[nq]) * c;
@@ -291,13 +280,6 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   // The steady loop never touches O except through the matrix pipe.  When some row of the wave has to
   // raise its running maximum the loop is left, O and l are rescaled, and the loop is entered again.
   typedef FragReader<KT, T> RD;
-#ifdef S1F_TRACE
-  unsigned long long trace_t[8] = {};
-  const bool trace_on = a.trace != nullptr && blockIdx.x == a.trace_wg && tid == a.trace_tid;
-#define S1F_TRACE_ARGS , trace_on, trace_t
-#else
-#define S1F_TRACE_ARGS
-#endif
   int k = 0;
   // Ring stages of the tiles holding block k (st_cur) and block k + 1 (st_next), and the tile that the next copy
   // fills: its first K and V rows, the rows of the prefix from there on, its stage.
@@ -308,14 +290,9 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
     bool raise_any = false;
     while (k + 1 < n_blk) {
       const int kb = k % KB;
-      S1F_TRACE_MARK(0);
       if (kb == KB - 1) {
         wait_async_tiles();   // this wave's part of the next tile has landed (it was issued a whole tile ago)
-#ifdef S1F_TRACE
-        S1F_TRACE_MARK(5);
-#endif
         __syncthreads();      // ... and everyone's; every wave has also finished reading the previous tile
-        S1F_TRACE_MARK(6);
       }
       // the tile two ahead of block k's (for kb = KB-1; the later parts follow in the steps of the next tile) goes
       // to the stage of the tile before block k's
@@ -331,21 +308,13 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
           v_iss += (int64_t)BN * a.kv_ss;
         }
       }
-      S1F_TRACE_MARK(1);
       const lds_addr vblock = lds0 + st_cur * Cfg::STAGE_BYTES + KT::BYTES + kb * BLOCK_BYTES;
       const int kn = k + 1;
       const lds_addr kblock_next = lds0 + st_next * Cfg::STAGE_BYTES + (kn % KB) * BLOCK_BYTES;
       const int lim0n = seg_off + wrow0 + ln - 32 * kn - 4 * g;
       // the last block always crosses the diagonal; earlier ones do if their last key is past the wave's first row
       const bool mask_next = kn + 1 == n_blk || 32 * kn + 31 > seg_off + wrow0;
-      fwd_step<RD, T, true>(s, sn, o, m, l, mx, qf, rd, kblock_next, vblock, c, mask_next, lim0n S1F_TRACE_ARGS);
-      S1F_TRACE_MARK(4);
-#ifdef S1F_TRACE
-      if (trace_on && k >= 300 && k < 364) {
-        unsigned long long *dst = a.trace + (size_t)(k - 300) * 8;
-        for (int i = 0; i < 7; ++i) dst[i] = trace_t[i];
-      }
-#endif
+      fwd_step<RD, T, true>(s, sn, o, m, l, mx, qf, rd, kblock_next, vblock, c, mask_next, lim0n);
       k = kn;
       st_cur = st_next;
       if ((k + 1) % KB == 0) st_next = st_next == 2 ? 0 : st_next + 1;
@@ -370,7 +339,7 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   }
   {   // last block: no next scores to compute
     const lds_addr vblock = lds0 + st_cur * Cfg::STAGE_BYTES + KT::BYTES + (k % KB) * BLOCK_BYTES;
-    fwd_step<RD, T, false>(s, sn, o, m, l, mx, qf, rd, vblock, vblock, c, false, 0 S1F_TRACE_ARGS);
+    fwd_step<RD, T, false>(s, sn, o, m, l, mx, qf, rd, vblock, vblock, c, false, 0);
   }
 
   T *ob = reinterpret_cast<T *>(a.out_w) + b * a.q_sb + h * a.q_sh;

@@ -104,7 +104,7 @@ extern "C" int s1f_seq1f1b_interleaved_order(int32_t pp_size, int32_t device, in
 }
 
 extern "C" int s1f_pipeline_simulate(const s1f_pipeline_desc *desc, int64_t *makespan, int64_t *busy,
-                                     int64_t *peak_live, int64_t *peak_pending_wgrad) {
+                                     int64_t *peak_live, int64_t *peak_pending_wgrad, double *bubble_ratio) {
   if (!desc || !makespan || !busy || !peak_live || !desc->t_fwd || !desc->t_bwd || desc->reserved != 0)
     return S1F_EINVAL;
   if (!valid(desc->pp_size, 1, desc->n_micro, desc->n_seg, desc->n_chunks)) return S1F_EINVAL;
@@ -199,13 +199,17 @@ extern "C" int s1f_pipeline_simulate(const s1f_pipeline_desc *desc, int64_t *mak
     if (!moved) return S1F_EUNSUPPORTED;   // dead-lock: cannot happen with the orders generated above
   }
   *makespan = 0;
+  int64_t busy_sum = 0;
   for (int64_t d = 0; d < s.P; ++d) {
     Device &dv = dev[(size_t)d];
     while (dv.pending_head < dv.pending.size()) run_wgrad(dv);
     if (dv.free_at > *makespan) *makespan = dv.free_at;
     busy[d] = dv.busy;
+    busy_sum += dv.busy;
     peak_live[d] = dv.peak_live;
     if (peak_pending_wgrad) peak_pending_wgrad[d] = dv.peak_pending;
   }
+  // share of the devices' time spent idle: 1 - sum(busy) / (P * makespan)
+  if (bubble_ratio) *bubble_ratio = *makespan > 0 ? 1.0 - (double)busy_sum / ((double)s.P * (double)*makespan) : 0.0;
   return S1F_OK;
 }

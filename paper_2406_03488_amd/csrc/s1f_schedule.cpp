@@ -45,3 +45,18 @@ extern "C" int s1f_seq1f1b_order(int32_t pp_size, int32_t device, int32_t n_micr
   for (int64_t t = total - w; t < total; ++t) backward(t);         // cooling-down phase
   return S1F_OK;
 }
+
+// Share of a batch's intermediate states that device i holds at its peak (Section 3.1: A * w_i / sum_j w_j for
+// total activation memory A), as the exact fraction w_i / sum_j w_j of the warm-up counts of Eq. 4 (Eq. 1 for
+// n_seg = 1).  For M > P the cap of the warm-up count at M * k never binds (M * k >= (P + 1) k > P + k - 2), so
+// the sum has the closed form P (P - 1) / 2 + P (k - 1); for M <= P every device holds everything: 1 / P.
+extern "C" int s1f_seq1f1b_peak_memory_share(int32_t pp_size, int32_t device, int32_t n_micro, int32_t n_seg,
+                                             int64_t *numerator, int64_t *denominator) {
+  if (!valid(pp_size, device, n_micro, n_seg) || !numerator || !denominator) return S1F_EINVAL;
+  const int64_t P = pp_size, k = n_seg;
+  const int64_t den = n_micro <= pp_size ? P * (int64_t)n_micro * k : P * (P - 1) / 2 + P * (k - 1);
+  if (den == 0) return S1F_EINVAL;   // one device, whole sequences: no warm-up phase anywhere, the share is undefined
+  *numerator = warmup_of(pp_size, device, n_micro, n_seg);
+  *denominator = den;
+  return S1F_OK;
+}

@@ -226,6 +226,35 @@ def test_seq1f1b_order_matches_oracle():
                     assert s1f.seq1f1b_order(P_, i, M, k) == SCH.stage_order(P_, i, M, k), (P_, i, M, k)
 
 
+def test_peak_memory_share_matches_oracle():
+    """Section 3.1's A * w_i / sum_j w_j: the library's closed-form denominator against the oracle's explicit sum,
+    as exact fractions and as the very same float."""
+    from fractions import Fraction
+    from oracle import schedule as SCH
+    for P_ in (1, 2, 3, 4, 8, 16):
+        for M in (1, 2, 4, 8, 9, 16, 17, 64):
+            for k in (1, 2, 3, 4, 8, 32):
+                total = Fraction(0)
+                ws = [SCH.warmup_count(P_, j, M, k) for j in range(1, P_ + 1)]
+                if sum(ws) == 0:            # one device, whole sequences: the formula divides by zero
+                    with pytest.raises(s1f.S1FError):
+                        s1f.seq1f1b_peak_memory_share(P_, 1, M, k)
+                    continue
+                for i in range(1, P_ + 1):
+                    num, den = s1f.seq1f1b_peak_memory_share(P_, i, M, k)
+                    assert (num, den) == (ws[i - 1], sum(ws)), (P_, i, M, k)
+                    assert num / den == SCH.peak_memory_fraction(P_, i, M, k)
+                    total += Fraction(num, den)
+                assert total == 1
+    # the paper's own example shape: 8 devices, 4 segments: the first device holds the most, shares fall by 1 / den
+    shares = [s1f.seq1f1b_peak_memory_share(8, i, 32, 4) for i in range(1, 9)]
+    assert [n for n, _ in shares] == [10, 9, 8, 7, 6, 5, 4, 3] and {d for _, d in shares} == {52}
+    with pytest.raises(s1f.S1FError):
+        s1f.seq1f1b_peak_memory_share(4, 5, 8, 2)
+    lib = s1f.load_library()
+    assert lib.s1f_seq1f1b_peak_memory_share(4, 1, 8, 2, None, None) == 1
+
+
 def test_seq1f1b_rejects_bad_arguments():
     for bad in ((0, 1, 4, 2), (4, 0, 4, 2), (4, 5, 4, 2), (4, 1, 0, 2), (4, 1, 4, 0)):
         with pytest.raises(s1f.S1FError) as e:

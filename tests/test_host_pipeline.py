@@ -101,4 +101,4 @@ def test_timeline_errors():
         s1f.pipeline_simulate(**{**ok, "n_chunks": 2, "n_seg": 3, "t_fwd": [1] * 3, "t_bwd": [1] * 3})
     assert e.value.status == 2
     lib = s1f.load_library()
-    assert lib.s1f_pipeline_simulate(None, None, None, None, None) == 1
+    assert lib.s1f_pipeline_simulate(None, None, None, None, None, None) == 1
