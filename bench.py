@@ -6,7 +6,11 @@ every segment in order, the zero-fill of the fp32 dK/dV accumulators, and the ba
 in reverse order (Sections 3.1, 3.2 and 3.4 of the Seq1F1B paper).  Inputs are resident in HBM before
 the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b|2.7b|30b|30b-uniform|gqa|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gqa|30b|7b|2.7b|30b-uniform|tiny]
+
+The headline workload is the largest one of the contract that fits one GPU (gqa: 131072 tokens, 32 segments, 64
+query heads on 8 K/V heads); the 7b and 30b workloads are run briefly in the same command and reported under
+"other_workloads".
 """
 import argparse
 import json
@@ -26,9 +30,15 @@ PEAK_F32_TFLOPS = 157.3     # MI355X fp32 matrix
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="7b")
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="gqa")
+    ap.add_argument("--others", default="7b,30b", help="workloads reported briefly next to the headline ('' for none)")
+    ap.add_argument("--constant-data", action="store_true",
+                    help="fill Q, K, V and dO with one constant instead of N(0,1): same instructions, hardly a bit "
+                         "toggling (shows how much of the kernels' time is the chip's power limit)")
+    ap.add_argument("--probe-atomics", action="store_true",
+                    help="also measure the rate of fp32 global atomic adds in the access shape a fused dQ would use")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unsegmented", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the replay of the step recorded as one HIP graph")
@@ -82,10 +92,13 @@ def measured_mfma_peak(torch):
     return best
 
 
+KERNEL_NAMES = {"fwd": "seg_attn_fwd_kernel", "bwd_dq": "seg_attn_bwd_dq_kernel", "bwd_dkdv": "seg_attn_bwd_dkdv_kernel"}
+
+
 class Stage:
     """Device buffers of one pipeline stage's attention for one sequence, and the step that uses them."""
 
-    def __init__(self, w, torch, s1f):
+    def __init__(self, w, torch, s1f, constant_data=False):
         self.w, self.torch, self.s1f = w, torch, s1f
         dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         gen = torch.Generator(device="cuda")
@@ -93,6 +106,8 @@ class Stage:
         n, d = w.seq_len, w.head_dim
 
         def rnd(h):
+            if constant_data:
+                return torch.full((1, h, n, d), 0.5, device="cuda", dtype=dt)
             return torch.randn((1, h, n, d), generator=gen, device="cuda", dtype=torch.float32).to(dt)
 
         self.q, self.dout = rnd(w.n_q_heads), rnd(w.n_q_heads)
@@ -219,7 +234,7 @@ def balance_report(stage, w, seg_ms, bounds, kernels, args):
     rep = {"partition": w.partition, "this": ratio(bounds, seg_ms), "linear_term": "modelled, not measured"}
     if w.partition != "cwp":
         return rep
-    steps = max(2, args.steps // 3)
+    steps = 2
 
     def measure(kind):
         stage.events = []
@@ -253,40 +268,115 @@ def graph_report(stage, torch, flops, steps):
         stage.step()
     graph.replay()
     torch.cuda.synchronize()
+    steps = min(steps, 5)
     t0 = time.perf_counter()
     for _ in range(steps):
         graph.replay()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
-    return {"ms_per_step": ms, "tflops": flops / (ms * 1e-3) / 1e12}
+    return {"ms_per_step": ms, "tflops": flops / (ms * 1e-3) / 1e12, "replays": steps}
 
 
 def cpu_baseline(stage, torch):
-    """The row oracle, as it stands, timed on this machine's host cores on a bounded sample of the workload:
-    the first `ns` tokens of a few heads, full causal forward + backward (about 5e8 (query, key) pairs)."""
+    """The row oracle, as it stands, timed on this machine's host cores on a bounded sample of the workload: one K/V
+    group (its query heads share one K/V head, as in the workload) over the first `ns` tokens, full causal
+    forward + backward, `ns` chosen for about 5e8 (query, key) pairs in all."""
     from oracle import rows
     w = stage.w
-    ns = min(w.seq_len, 32768)
-    pairs = ns * (ns + 1) // 2
-    heads = max(1, min(w.n_q_heads, round(5.4e8 / pairs)))
     grp = w.n_q_heads // w.n_kv_heads
+    ns = min(w.seq_len, int(math.sqrt(2 * 5.4e8 / grp)))
+    pairs = ns * (ns + 1) // 2
     rows.build()
-    dt = 0.0
-    for h in range(heads):
-        g = h // grp
-        q = stage.q[0, h:h + 1, :ns].float().cpu().numpy()
-        do = stage.dout[0, h:h + 1, :ns].float().cpu().numpy()
-        k = stage.k[0, g:g + 1, :ns].float().cpu().numpy()
-        v = stage.v[0, g:g + 1, :ns].float().cpu().numpy()
-        t0 = time.perf_counter()
-        rows.forward_rows(q, k, v, 0, 0, ns)
-        rows.dq_rows(q, k, v, do, 0, 0, ns)
-        rows.dkdv_keys(q, k, v, do, 0, 0, ns)
-        dt += time.perf_counter() - t0
-    flops = 14.0 * w.head_dim * pairs * heads
+    q = stage.q[0, :grp, :ns].float().cpu().numpy()
+    do = stage.dout[0, :grp, :ns].float().cpu().numpy()
+    k = stage.k[0, :1, :ns].float().cpu().numpy()
+    v = stage.v[0, :1, :ns].float().cpu().numpy()
+    t0 = time.perf_counter()
+    for h in range(grp):
+        rows.forward_rows(q, k, v, h, 0, ns)
+        rows.dq_rows(q, k, v, do, h, 0, ns)
+    rows.dkdv_keys(q, k, v, do, 0, 0, ns)
+    dt = time.perf_counter() - t0
+    flops = 14.0 * w.head_dim * pairs * grp
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": rows.threads(), "kind": "oracle",
-            "sample": f"fp64 row oracle, {heads} head(s), first {ns} tokens of the {w.name} workload, full causal "
-                      f"forward+backward ({dt:.1f} s)", "seconds": dt}
+            "sample": f"fp64 row oracle, one K/V group ({grp} query head(s) on 1 K/V head), first {ns} tokens of the "
+                      f"{w.name} workload, full causal forward+backward ({dt:.1f} s)", "seconds": dt}
+
+
+def measure_workload(w, torch, s1f, steps, warmup, constant_data=False):
+    """Runs `steps` timed steps of workload w.  Returns (stage, result dict with the headline fields)."""
+    stage = Stage(w, torch, s1f, constant_data)
+    ms = stage.run(steps, warmup)
+    bounds = stage.boundaries()
+    pairs = seg_pairs(bounds)
+    d, hq = w.head_dim, w.n_q_heads
+    tot_pairs = sum(pairs)
+    assert tot_pairs == w.seq_len * (w.seq_len + 1) // 2
+    flops = 14.0 * d * hq * tot_pairs
+    peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
+    # per-kernel durations from the events recorded inside the timed steps
+    per = {"fwd": [0.0, 0, 4.0], "bwd_dq": [0.0, 0, 2.0], "bwd_dkdv": [0.0, 0, 8.0]}   # ms, launches, flops/(pair*D)
+    seg_ms = {}
+    for kind, i, e0, e1 in stage.events:
+        t = e0.elapsed_time(e1)
+        per[kind][0] += t; per[kind][1] += 1
+        seg_ms.setdefault(kind, [0.0] * len(pairs))[i] += t / steps
+    kernels = {}
+    for kind, (t, cnt, fpp) in per.items():
+        alg = fpp * d * hq * tot_pairs * steps          # algorithmic flops over all timed launches
+        kernels[kind] = {"avg_launch_ms": t / cnt, "launches_per_step": cnt // steps,
+                         "alg_tflops": alg / (t * 1e-3) / 1e12, "ms_per_step": t / steps}
+    # executed rate of the dQ kernel: it runs three products (S, dP, dQ) where one is credited
+    kernels["bwd_dq"]["executed_tflops"] = 3.0 * kernels["bwd_dq"]["alg_tflops"]
+    sm = stage.step_ms
+    mean = sum(sm) / len(sm)
+    res = {"value": flops / (ms * 1e-3) / 1e12, "ms_per_step": ms, "pct_of_peak": 100.0 * flops / (ms * 1e-3) / 1e12 / peak,
+           "config": {"workload": w.name, "seq_len": w.seq_len, "n_seg": w.n_seg, "partition": w.partition,
+                      "n_q_heads": hq, "n_kv_heads": w.n_kv_heads, "head_dim": d, "boundaries": bounds},
+           "fwd_tflops": 4.0 * d * hq * tot_pairs / (kernels["fwd"]["ms_per_step"] * 1e-3) / 1e12,
+           "bwd_tflops": 10.0 * d * hq * tot_pairs /
+                         ((kernels["bwd_dq"]["ms_per_step"] + kernels["bwd_dkdv"]["ms_per_step"]) * 1e-3) / 1e12,
+           "kernels": kernels, "segment_ms": seg_ms, "step_ms_mean": mean,
+           "step_ms_std": (sum((x - mean) ** 2 for x in sm) / max(1, len(sm) - 1)) ** 0.5}
+    return stage, res, flops, peak
+
+
+def unsegmented_report(stage, ms, steps):
+    """One unsegmented pass (a single segment at offset 0) over the same sequence, and what segmentation costs."""
+    stage.events = []
+    ms1 = stage.run(steps, 1, n_seg=1, kind="uniform")
+    per_kernel = {}
+    for kind, _, e0, e1 in stage.events:
+        per_kernel[kind] = per_kernel.get(kind, 0.0) + e0.elapsed_time(e1) / steps
+    return {"unsegmented_ms": ms1, "segmentation_overhead": ms / ms1 - 1.0, "unsegmented_kernels_ms": per_kernel}
+
+
+def atomics_probe(torch):
+    """TB/s of fp32 global atomic adds (and of plain stores of the same shape) when every wave adds 32 rows x 32
+    floats per step into a [rows, 128] fp32 array shared by the workgroups of a head, heads spread over the XCDs the
+    way the kernels spread them: the traffic a dK/dV kernel that also produced dQ would put on the L2."""
+    import ctypes
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2406_03488_amd", "libs1f_probe.so"))
+    lib.s1f_probe_dq_atomics.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                         ctypes.c_void_p, ctypes.c_void_p]
+    lib.s1f_probe_dq_atomics.restype = ctypes.c_int
+    rows, heads, steps, wgs = 4096, 32, 128, 2048
+    acc = torch.zeros(heads * rows * 128, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {}
+    for mode, name in ((0, "atomic_add_f32_TB_per_s"), (1, "plain_store_TB_per_s")):
+        best = 0.0
+        for rep in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            if lib.s1f_probe_dq_atomics(wgs, rows, heads, steps, mode, acc.data_ptr(), stream) != 0:
+                raise RuntimeError("atomics probe failed to launch")
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, wgs * 4 * steps * 16 * 64 * 4.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        out[name] = best
+    out["shape"] = f"{wgs} workgroups x 4 waves x {steps} steps x 16 instructions of 64 lanes x 4 bytes"
+    return out
 
 
 def main():
@@ -309,54 +399,25 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    stage = Stage(w, torch, s1f)
-    ms = stage.run(args.steps, args.warmup)
-    bounds = stage.boundaries()
-    pairs = seg_pairs(bounds)
-    d, hq = w.head_dim, w.n_q_heads
-    tot_pairs = sum(pairs)
-    assert tot_pairs == w.seq_len * (w.seq_len + 1) // 2
-    flops = 14.0 * d * hq * tot_pairs
-    peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
+    stage, res, flops, peak = measure_workload(w, torch, s1f, args.steps, args.warmup, args.constant_data)
+    ms, bounds, kernels, seg_ms = res["ms_per_step"], res["config"]["boundaries"], res["kernels"], res["segment_ms"]
 
-    # per-kernel durations from the events recorded inside the timed steps
-    per = {"fwd": [0.0, 0, 4.0], "bwd_dq": [0.0, 0, 2.0], "bwd_dkdv": [0.0, 0, 8.0]}   # ms, launches, flops/(pair*D)
-    seg_ms = {}
-    for kind, i, e0, e1 in stage.events:
-        t = e0.elapsed_time(e1)
-        per[kind][0] += t; per[kind][1] += 1
-        seg_ms.setdefault(kind, [0.0] * len(pairs))[i] += t / args.steps
-    kernels = {}
-    for kind, (t, cnt, fpp) in per.items():
-        alg = fpp * d * hq * tot_pairs * args.steps          # algorithmic flops over all timed launches
-        kernels[kind] = {"avg_launch_ms": t / cnt, "launches_per_step": cnt // args.steps,
-                         "alg_tflops": alg / (t * 1e-3) / 1e12, "ms_per_step": t / args.steps}
     dom = max(kernels, key=lambda kk: kernels[kk]["ms_per_step"])
-    roofline = {"bound": "mfma", "kernel": {"fwd": "seg_attn_fwd_kernel", "bwd_dq": "seg_attn_bwd_dq_kernel",
-                                            "bwd_dkdv": "seg_attn_bwd_dkdv_kernel"}[dom],
+    roofline = {"bound": "mfma", "kernel": KERNEL_NAMES[dom],
                 "achieved": kernels[dom]["alg_tflops"], "peak": peak, "unit": "TFLOP/s",
-                "frac": kernels[dom]["alg_tflops"] / peak, "traffic": None, "traffic_unit": "bytes per launch",
-                "avg_launch_ms": kernels[dom]["avg_launch_ms"]}
-
-    roofline["traffic"] = measured_traffic(roofline["kernel"], w.name)
-
+                "frac": kernels[dom]["alg_tflops"] / peak, "traffic": measured_traffic(KERNEL_NAMES[dom], w.name),
+                "traffic_unit": "bytes per launch", "avg_launch_ms": kernels[dom]["avg_launch_ms"]}
     result = {
         "metric": "segmented causal attn fwd+bwd TFLOP/s on 1 GPU; % of bf16 MFMA peak",
-        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "value": res["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "seq_len": w.seq_len, "n_seg": w.n_seg, "partition": w.partition,
-                   "n_q_heads": hq, "n_kv_heads": w.n_kv_heads, "head_dim": d, "boundaries": bounds},
-        "pct_of_peak": 100.0 * flops / (ms * 1e-3) / 1e12 / peak,
-        "fwd_tflops": 4.0 * d * hq * tot_pairs / (kernels["fwd"]["ms_per_step"] * 1e-3) / 1e12,
-        "bwd_tflops": 10.0 * d * hq * tot_pairs /
-                      ((kernels["bwd_dq"]["ms_per_step"] + kernels["bwd_dkdv"]["ms_per_step"]) * 1e-3) / 1e12,
-        "kernels": kernels, "segment_ms": seg_ms, "roofline": roofline,
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic, constant" if args.constant_data else "synthetic",
+        "config": res["config"], "pct_of_peak": res["pct_of_peak"], "fwd_tflops": res["fwd_tflops"],
+        "bwd_tflops": res["bwd_tflops"], "kernels": kernels, "segment_ms": seg_ms, "roofline": roofline,
+        "step_ms_mean": res["step_ms_mean"], "step_ms_std": res["step_ms_std"],
     }
-    sm = stage.step_ms
-    mean = sum(sm) / len(sm)
-    result["step_ms_mean"] = mean
-    result["step_ms_std"] = (sum((x - mean) ** 2 for x in sm) / max(1, len(sm) - 1)) ** 0.5
+    for kind in kernels:
+        kernels[kind]["traffic_bytes_per_launch"] = measured_traffic(KERNEL_NAMES[kind], w.name)
     if not args.no_mfma_probe and w.dtype == "bf16":
         mp, mp_varied = measured_mfma_peak(torch)
         result["measured_mfma_peak_tflops"] = mp
@@ -365,23 +426,34 @@ def main():
         result["pct_of_measured_peak_varied_data"] = 100.0 * result["value"] / mp_varied
         roofline["frac_of_measured_peak"] = roofline["achieved"] / mp
         roofline["frac_of_measured_peak_varied_data"] = roofline["achieved"] / mp_varied
+    if args.probe_atomics:
+        result["dq_atomics_probe"] = atomics_probe(torch)
     result["cache_kernels"] = cache_kernels_report(stage, w, torch, s1f, bounds)
     if not args.no_balance:
         result["balance"] = balance_report(stage, w, seg_ms, bounds, kernels, args)
     if not args.no_unsegmented:
-        stage.events = []
-        steps1 = max(2, args.steps // 3)
-        ms1 = stage.run(steps1, 1, n_seg=1, kind="uniform")
-        result["unsegmented_ms"] = ms1
-        result["segmentation_overhead"] = ms / ms1 - 1.0
-        per_kernel = {}
-        for kind, _, e0, e1 in stage.events:
-            per_kernel[kind] = per_kernel.get(kind, 0.0) + e0.elapsed_time(e1) / steps1
-        result["unsegmented_kernels_ms"] = per_kernel   # against kernels[*].ms_per_step: where the overhead sits
+        result.update(unsegmented_report(stage, ms, 2))
     if not args.no_graph:
         result["hip_graph"] = graph_report(stage, torch, flops, args.steps)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(stage, torch)
+    del stage
+    torch.cuda.empty_cache()
+    # the other workloads of the target range, briefly: same step, same kernels
+    others = {}
+    for name in [x for x in args.others.split(",") if x and x != w.name]:
+        st2, r2, _, _ = measure_workload(S.WORKLOADS[name], torch, s1f, 3, 1, args.constant_data)
+        if not args.no_unsegmented:
+            r2.update(unsegmented_report(st2, r2["ms_per_step"], 2))
+        r2["kernels"] = {k: {"alg_tflops": v["alg_tflops"], "ms_per_step": v["ms_per_step"],
+                             "avg_launch_ms": v["avg_launch_ms"]} for k, v in r2["kernels"].items()}
+        r2["config"] = {k: v for k, v in r2["config"].items() if k != "boundaries"}
+        del r2["segment_ms"]
+        others[name] = r2
+        del st2
+        torch.cuda.empty_cache()
+    if others:
+        result["other_workloads"] = others
     print(json.dumps(result))
 
 

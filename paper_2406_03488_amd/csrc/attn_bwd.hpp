@@ -406,6 +406,18 @@ __global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kerne
     }
   };
 
+  // End of an iteration: the wave's share of the NEXT tile must have landed.  With DIST = 2 the copy issued at the top
+  // of this iteration (PER instructions, one more for the statistics on wave 0) belongs to the tile after it and
+  // stays in flight across the barrier.
+  constexpr int kCopyInsts = AsyncTilePairU<T, BQ, D, NW>::PER;
+  auto wait_next_tile = [&](bool issued_this_iteration) {
+    if (DIST >= 2 && issued_this_iteration) {
+      if (wave < 2 * BQ / 64) wait_async_tiles_but_last<kCopyInsts + 1>();
+      else wait_async_tiles_but_last<kCopyInsts>();
+    } else {
+      wait_async_tiles();
+    }
+  };
   Cursor cur = {qt_first * BQ, hk * a.group, 0};   // tile of the current iteration
   const bool late = LAG > 0 && wave >= NW / 2;
   if (!late) {
@@ -420,7 +432,7 @@ __global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kerne
         phase_d(z, cur);
       }
       advance(cur);
-      wait_async_tiles();   // this wave's part of tile it+DIST has landed
+      wait_next_tile(it + DIST < n_it);   // this wave's part of tile it+1 has landed
       __syncthreads();
     }
   } else {
@@ -436,7 +448,7 @@ __global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kerne
       if (active(cur)) phase_b(z, cur);
       prev = cur;
       advance(cur);
-      wait_async_tiles();
+      wait_next_tile(it + DIST < n_it);
       __syncthreads();
     }
     if (active(prev)) {
@@ -445,27 +457,47 @@ __global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kerne
     }
   }
 
+  // Epilogue: acc[key][d] += result, each element touched by exactly one lane of the grid.  In the accumulators a
+  // lane holds ONE key and 4-element pieces of its row 32 bytes apart: read-modify-write straight from there would
+  // touch 64 different cache lines per instruction.  Each wave therefore passes its 32 x D block through LDS (its
+  // own region; rows padded by 16 bytes so that the row-per-lane writes spread over all banks) and updates the
+  // accumulators row by row, LPR lanes side by side on one row.
+  __syncthreads();   // the late half's last phases still read the tile ring that the regions below overlay
   float *dkb = a.dk_acc + kvoff, *dvb = a.dv_acc + kvoff;
-  {
-    const int key = wkey0 + ln;
-    if (key < kv_len) {
-      float *dkr = dkb + (int64_t)key * a.kv_ss, *dvr = dvb + (int64_t)key * a.kv_ss;
+  constexpr int ROWB = QT::DPAD * 4 + 16;           // bytes per staged row
+  constexpr int LPR = D / 4;                        // lanes per row (16 bytes each)
+  constexpr int RPI = 64 / LPR;                     // rows per instruction
+  constexpr int NI = (32 + RPI - 1) / RPI;          // instructions per block
+  static_assert(NW * 32 * ROWB <= Cfg::LDS_BYTES, "the epilogue's staging regions must fit the kernel's LDS");
+  char *region = smem + wave * (32 * ROWB);
+  const int row_in = lane / LPR, col = lane % LPR;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+  for (int which = 0; which < 2; ++which) {
+    const f32x16(&acc)[DB] = which == 0 ? dk : dv;
+    const float mul = which == 0 ? a.scale : 1.f;
+    float *base = which == 0 ? dkb : dvb;
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          const int d0 = 32 * db + 8 * vq + 4 * g;
-          if (d0 < D) {
-            f32x4 x = *reinterpret_cast<f32x4 *>(dkr + d0), y = *reinterpret_cast<f32x4 *>(dvr + d0);
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              x[e] += dk[db][4 * vq + e] * a.scale;
-              y[e] += dv[db][4 * vq + e];
-            }
-            *reinterpret_cast<f32x4 *>(dkr + d0) = x;
-            *reinterpret_cast<f32x4 *>(dvr + d0) = y;
-          }
-        }
+      for (int vq = 0; vq < 4; ++vq) {
+        const int d0 = 32 * db + 8 * vq + 4 * g;
+        *reinterpret_cast<f32x4 *>(region + ln * ROWB + d0 * 4) =
+            f32x4{acc[db][4 * vq] * mul, acc[db][4 * vq + 1] * mul, acc[db][4 * vq + 2] * mul, acc[db][4 * vq + 3] * mul};
+      }
+    f32x4 cur[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int r = i * RPI + row_in, key = wkey0 + r;
+      if (row_in < RPI && r < 32 && key < kv_len)
+        cur[i] = *reinterpret_cast<const f32x4 *>(base + (int64_t)key * a.kv_ss + 4 * col);
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int r = i * RPI + row_in, key = wkey0 + r;
+      if (row_in < RPI && r < 32 && key < kv_len) {
+        const f32x4 add = *reinterpret_cast<const f32x4 *>(region + r * ROWB + 16 * col);
+        *reinterpret_cast<f32x4 *>(base + (int64_t)key * a.kv_ss + 4 * col) = cur[i] + add;
+      }
     }
   }
 }

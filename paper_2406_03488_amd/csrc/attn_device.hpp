@@ -432,6 +432,8 @@ template <typename V> S1F_DEV void settle(V &v) { asm volatile("" : "+v"(v)); }
 
 // Wait until every asynchronous tile copy issued by this wave has landed (vmcnt(0), other counters untouched).
 S1F_DEV void wait_async_tiles() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// The same, except that the wave's N most recent copy instructions may still be in flight (loads complete in order).
+template <int N> S1F_DEV void wait_async_tiles_but_last() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }
 
 // Store 4 consecutive head_dim elements of one row.
 template <typename T> S1F_DEV void store4(T *p, float a, float b, float c, float d);
@@ -446,20 +448,22 @@ template <> S1F_DEV void store4<bf16_t>(bf16_t *p, float a, float b, float c, fl
 // Workgroup id -> (tile, batch*head).  The hardware hands consecutive workgroup ids to the 8 XCDs in turn,
 // and each XCD has its own L2.  All tiles of one (batch, head) stream the same K/V prefix (or the same
 // Q/dO segment), so they are given ids that land on one XCD: the shared operand is then fetched from HBM once
-// per XCD instead of once per workgroup.  Within an XCD the ids run head by head (`tile_major` = 0: best when
-// the tiles of a launch take about the same time, i.e. behind a long prefix) or tile by tile over the XCD's
+// per XCD instead of once per workgroup.  An XCD takes n_bh / 8 CONSECUTIVE (batch, head) pairs, so that query
+// heads sharing a K/V head share an XCD as well.  Within an XCD the ids run head by head (`tile_major` = 0: best
+// when the tiles of a launch take about the same time, i.e. behind a long prefix) or tile by tile over the XCD's
 // heads (`tile_major` = 1: the light tiles of every head come last, which shortens the end of a launch whose
-// tiles differ a lot, i.e. the first segments).  Falls back to the plain order when the number of (batch, head)
-// pairs is not a multiple of 8.
+// tiles differ a lot, i.e. the first segments; and heads that share K/V rows walk them together).  Falls back to
+// the plain order when the number of (batch, head) pairs is not a multiple of 8.
 S1F_DEV void decode_workgroup(int id, int n_tiles, int n_bh, int tile_major, int &tile, int &bh) {
   if ((n_bh & 7) == 0) {
     const int xcd = id & 7, slot = id >> 3;
+    const int per_xcd = n_bh >> 3;
+    const int first = xcd * per_xcd;
     if (tile_major) {
-      const int per_xcd = n_bh >> 3;
-      bh = xcd + 8 * (slot % per_xcd);
+      bh = first + slot % per_xcd;
       tile = slot / per_xcd;
     } else {
-      bh = xcd + 8 * (slot / n_tiles);
+      bh = first + slot / n_tiles;
       tile = slot % n_tiles;
     }
   } else {

@@ -1,7 +1,10 @@
-// Measurement aid for bench.py, not part of the attention path: register-resident back-to-back
+// Measurement aids for bench.py, not part of the attention path.
+// (1) Register-resident back-to-back
 // v_mfma_f32_32x32x16_bf16 on every SIMD of the chip, to quote the kernels' rate against a measured matrix
 // peak next to the vendor figure: once with operands that never change and once with operands that toggle the
-// datapath like real activations (the chip clocks lower then).  Built into its own small library.
+// datapath like real activations (the chip clocks lower then).
+// (2) The rate of fp32 global atomic adds in the access shape a dK/dV kernel would need to accumulate dQ as well
+// (the measurement behind keeping dQ in a kernel of its own).  Built into their own small library.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -68,5 +71,43 @@ extern "C" int s1f_probe_mfma_bf16(int workgroups, int iters, int varied_data, f
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   if (varied_data) hipLaunchKernelGGL(mfma_peak_kernel<true>, dim3((unsigned)workgroups), dim3(256), 0, st, sink, iters);
   else hipLaunchKernelGGL(mfma_peak_kernel<false>, dim3((unsigned)workgroups), dim3(256), 0, st, sink, iters);
+  return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+namespace {
+// Each wave adds (mode 0: atomically; mode 1: plain stores, for comparison) 32 rows x 32 floats per step, rows
+// 512 bytes apart, walking over a [rows x 128] fp32 array shared by the workgroups of one head; heads are spread
+// over the XCDs the way the attention kernels spread them (workgroup id modulo 8).
+__global__ void __launch_bounds__(256) dq_atomics_kernel(float *acc, int rows, int n_heads, int steps, int mode) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ln = lane & 31, g = lane >> 5;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int wg_per_head = gridDim.x / n_heads;
+  const int head = xcd + 8 * (slot / wg_per_head), wg = slot % wg_per_head;
+  float *base = acc + (size_t)head * rows * 128 + 32 * wave + ln;
+  int r0 = (wg * 97) % (rows / 32) * 32;   // workgroups of a head start at different tiles
+  for (int s = 0; s < steps; ++s) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = r0 + 8 * (v >> 2) + 4 * g + (v & 3);
+      float *p = base + (size_t)row * 128;
+      if (mode == 0) __builtin_amdgcn_global_atomic_fadd_f32(p, 1.0f);
+      else *p = 1.0f;
+    }
+    r0 += 32;
+    if (r0 >= rows) r0 = 0;
+  }
+}
+}  // namespace
+
+// `acc`: device memory of n_heads * rows * 128 floats.  workgroups and n_heads must be multiples of 8, workgroups a
+// multiple of n_heads, rows a multiple of 32.  Moves workgroups * 4 * steps * 16 * 64 * 4 bytes of updates.
+// Returns 0, or 1 on a bad argument or a launch failure.
+extern "C" int s1f_probe_dq_atomics(int workgroups, int rows, int n_heads, int steps, int mode, float *acc,
+                                    void *hip_stream) {
+  if (workgroups < 8 || n_heads < 8 || workgroups % 8 || n_heads % 8 || workgroups % n_heads || rows < 32 ||
+      rows % 32 || steps < 1 || (mode != 0 && mode != 1) || !acc)
+    return 1;
+  hipLaunchKernelGGL(dq_atomics_kernel, dim3((unsigned)workgroups), dim3(256), 0,
+                     reinterpret_cast<hipStream_t>(hip_stream), acc, rows, n_heads, steps, mode);
   return hipGetLastError() == hipSuccess ? 0 : 1;
 }

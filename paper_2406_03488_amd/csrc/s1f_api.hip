@@ -79,6 +79,14 @@ template <typename K> int prepare(K kernel, int lds_bytes) {
   return S1F_OK;
 }
 
+// Order of the row tiles of the forward and dQ kernels within an XCD.  Tile by tile over the XCD's heads when the
+// tiles of the launch differ a lot in length (a first segment: the light tiles of every head then come last), and
+// whenever query heads share K/V heads: an XCD then holds the query heads of one K/V group, and running the same
+// row tile of all of them side by side makes them stream the same K/V rows through its L2 at the same time.
+int row_tile_order(const s1f_desc *d, const AttnArgs &a) {
+  return 2 * (int64_t)a.seg_off < (int64_t)a.seg_len || d->n_q_heads > d->n_kv_heads;
+}
+
 // One-dimensional grid of n_tiles * n_bh workgroups; the kernels decode (tile, batch*head) themselves.
 // `tile_major`: order of the workgroups within an XCD; chosen per kernel from the shape of the segment.
 // With `enqueue` false only the one-time preparation runs, so that a caller of several kernels can finish
@@ -103,16 +111,14 @@ template <typename T, int D> int fwd_impl(const s1f_desc *d, const AttnArgs &a, 
   typedef Shape<T> S;
   typedef FwdCfg<T, D, S::FNQ, S::FKB, S::FNW> Cfg;
   return launch(seg_attn_fwd_kernel<T, D, S::FNQ, S::FKB, S::FNW, S::FOCC>, (a.seg_len + Cfg::BM - 1) / Cfg::BM,
-                (int64_t)d->n_q_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, Cfg::THREADS,
-                Cfg::LDS_BYTES, a, st, enqueue);
+                (int64_t)d->n_q_heads * d->batch, row_tile_order(d, a), Cfg::THREADS, Cfg::LDS_BYTES, a, st, enqueue);
 }
 
 template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
   typedef Shape<T> S;
   typedef BwdDqCfg<T, D, S::QNQ, S::QBN> QC;
   return launch(seg_attn_bwd_dq_kernel<T, D, S::QNQ, S::QBN, S::QOCC>, (a.seg_len + QC::BM - 1) / QC::BM,
-                (int64_t)d->n_q_heads * d->batch, 2 * (int64_t)a.seg_off < (int64_t)a.seg_len, 256, QC::LDS_BYTES, a, st,
-                enqueue);
+                (int64_t)d->n_q_heads * d->batch, row_tile_order(d, a), 256, QC::LDS_BYTES, a, st, enqueue);
 }
 
 template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
