@@ -117,7 +117,8 @@ class Stage:
         self.dk = torch.empty((1, w.n_kv_heads, n, d), device="cuda", dtype=torch.float32)
         self.dv = torch.empty_like(self.dk)
         self.lse_flat = torch.empty(w.n_q_heads * n, device="cuda", dtype=torch.float32)
-        self.ws = torch.empty(2 * w.n_q_heads * (n + 64), device="cuda", dtype=torch.float32)
+        self.ws = torch.empty(2 * w.n_q_heads * (n + 64) + (129 << 18), device="cuda", dtype=torch.float32)   # statistics + 129 MiB of partial rows
+        self.fwd_ws = torch.empty(130 << 20, device="cuda", dtype=torch.uint8)
         self.events = []     # (kind, segment, start, end) recorded inside timed steps
 
     def boundaries(self, n_seg=None, kind=None):
@@ -154,7 +155,8 @@ class Stage:
             self.events.append((kind_, i, e0, e1))
 
         for i, (a, b, lse) in enumerate(segs):
-            timed("fwd", i, lambda: s1f.seg_attn_fwd(self.q[:, :, a:b], self.k, self.v, a, self.out[:, :, a:b], lse))
+            timed("fwd", i, lambda: s1f.seg_attn_fwd_ws(self.q[:, :, a:b], self.k, self.v, a, self.out[:, :, a:b], lse,
+                                                         self.fwd_ws))
         self.dk.zero_(); self.dv.zero_()
         for i in reversed(range(len(segs))):
             a, b, lse = segs[i]

@@ -124,6 +124,22 @@ int s1f_partition_rebalance(int32_t n_seg, const int64_t *boundaries_in, const i
 int s1f_seg_attn_fwd(const s1f_desc *desc, const void *q_seg, const void *k_prefix, const void *v_prefix,
                      int64_t seg_off, int64_t seg_len, void *out, float *lse, void *hip_stream);
 
+/* s1f_seg_attn_fwd with a caller-owned device workspace, which lets the library shorten the end of a launch: the
+ * method turns one long launch into n_seg short ones (Sections 3.1-3.2), and a short launch ends with most of the
+ * chip idle while its last few row tiles walk their whole prefix.  With a workspace the last row tiles are cut into
+ * chunks along the keys that run side by side; each chunk leaves an unnormalised partial result there and a small
+ * second kernel merges them by their log-sum-exp.  Same results up to fp32 rounding of that merge; bf16 only (fp32
+ * descriptors run unsplit).
+ *   workspace        device memory, 16-byte aligned, at least s1f_fwd_workspace_bytes(desc, seg_off, seg_len) bytes
+ *                    (0 when this launch is not split: workspace may then be NULL); contents undefined afterwards
+ * Errors as s1f_seg_attn_fwd, plus S1F_EINVAL if the workspace is too small, NULL or misaligned. */
+int s1f_seg_attn_fwd_ws(const s1f_desc *desc, const void *q_seg, const void *k_prefix, const void *v_prefix,
+                        int64_t seg_off, int64_t seg_len, void *out, float *lse, void *workspace,
+                        size_t workspace_bytes, void *hip_stream);
+/* Bytes s1f_seg_attn_fwd_ws needs for this call shape on the current device (0: none, or invalid arguments).  At most
+ * 129 MiB.  The answer depends on the device's compute-unit count, so ask on the device that will run the call. */
+size_t s1f_fwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len);
+
 /* Backward of one segment (derivative of Eq. 3; order and accumulation per Sections 3.1-3.2).
  *
  *   dout, q_seg, out, lse : the segment's upstream gradient and the tensors saved by the forward
@@ -136,7 +152,9 @@ int s1f_seg_attn_fwd(const s1f_desc *desc, const void *q_seg, const void *k_pref
  *             [seg_off, seg_off+seg_len) hold final gradients.
  *   workspace device scratch of at least s1f_bwd_workspace_bytes(desc, seg_off, seg_len) bytes
  *             (two fp32 values per query row and head: -lse/scale and -rowsum(dout * out), the row
- *             statistics the dK/dV kernel starts its products from); contents are undefined afterwards.
+ *             statistics the dK/dV kernel starts its products from; behind them up to 128 MiB of partial dQ
+ *             rows when the dQ kernel cuts its last row tiles into chunks along the keys, as
+ *             s1f_seg_attn_fwd_ws does); contents are undefined afterwards.
  * Errors as above, plus S1F_EINVAL if workspace is NULL or workspace_bytes is too small, and
  * S1F_EUNSUPPORTED if batch * n_q_heads * seg_len > 2^28 (the kernels' asynchronous copies use 32-bit byte
  * offsets inside the workspace). */
@@ -159,13 +177,17 @@ int s1f_seg_attn_bwd_dkdv(const s1f_desc *desc, const void *dout, const void *q_
                           float *dk_prefix_acc, float *dv_prefix_acc, const void *workspace,
                           size_t workspace_bytes, void *hip_stream);
 
-/* Bytes of device scratch s1f_seg_attn_bwd needs for this call shape (0 on invalid arguments). */
+/* Bytes of device scratch s1f_seg_attn_bwd needs for this call shape on the current device (0 on invalid
+ * arguments). */
 size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len);
 
 /* s1f_seg_attn_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
  * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments (without the
- * workspace), same kernels and bit-identical results; the row statistics go to a device array built into the
- * library (16 MiB per GPU, held until the process ends) instead of a caller-owned workspace.  The call
+ * workspace), same kernels; dK/dV bit-identical, dQ identical up to the rounding order of the key-split (the
+ * built-in scratch leaves room for 32 MiB of partial dQ rows, s1f_seg_attn_bwd's workspace for 128 MiB, so the
+ * two may cut a launch differently); the row statistics go to a device array built into the
+ * library (48 MiB per GPU: 16 MiB of row statistics and 32 MiB for partial dQ rows; held until the process ends)
+ * instead of a caller-owned workspace.  The call
  * allocates nothing and frees nothing.
  *   Limit: batch * n_q_heads * seg_len <= s1f_static_scratch_rows() (2^21); beyond it the call returns
  *   S1F_ESCRATCH before anything is launched.

@@ -67,6 +67,10 @@ def load_library():
     lib.s1f_partition_rebalance.restype = ctypes.c_int
     lib.s1f_seg_attn_fwd.argtypes = [dp, vp, vp, vp, i64, i64, vp, vp, vp]
     lib.s1f_seg_attn_fwd.restype = ctypes.c_int
+    lib.s1f_seg_attn_fwd_ws.argtypes = [dp, vp, vp, vp, i64, i64, vp, vp, vp, sz, vp]
+    lib.s1f_seg_attn_fwd_ws.restype = ctypes.c_int
+    lib.s1f_fwd_workspace_bytes.argtypes = [dp, i64, i64]
+    lib.s1f_fwd_workspace_bytes.restype = sz
     lib.s1f_seg_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
     lib.s1f_seg_attn_bwd.restype = ctypes.c_int
     lib.s1f_seg_attn_bwd_dq.argtypes = [dp, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
@@ -275,6 +279,28 @@ def seg_attn_fwd(q_seg, k_prefix, v_prefix, seg_off: int, out, lse):
                               int(seg_off), int(q_seg.shape[2]), out.data_ptr(), lse.data_ptr(), _stream_ptr())
     if rc != 0:
         raise S1FError(rc, "s1f_seg_attn_fwd")
+
+
+def fwd_workspace_bytes(q_seg, k_prefix, seg_off: int) -> int:
+    desc = make_desc(q_seg, k_prefix)
+    return int(load_library().s1f_fwd_workspace_bytes(ctypes.byref(desc), int(seg_off), int(q_seg.shape[2])))
+
+
+def seg_attn_fwd_ws(q_seg, k_prefix, v_prefix, seg_off: int, out, lse, workspace):
+    """s1f_seg_attn_fwd_ws on torch device tensors: seg_attn_fwd with a device workspace of at least
+    fwd_workspace_bytes(...) bytes (None is accepted when that is 0)."""
+    lib = load_library()
+    _same_layout(q_seg, out)
+    _same_layout(k_prefix, v_prefix)
+    _check_lse(lse, q_seg)
+    desc = make_desc(q_seg, k_prefix)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = lib.s1f_seg_attn_fwd_ws(ctypes.byref(desc), q_seg.data_ptr(), k_prefix.data_ptr(), v_prefix.data_ptr(),
+                                 int(seg_off), int(q_seg.shape[2]), out.data_ptr(), lse.data_ptr(), ws_ptr, ws_bytes,
+                                 _stream_ptr())
+    if rc != 0:
+        raise S1FError(rc, "s1f_seg_attn_fwd_ws")
 
 
 def bwd_workspace_bytes(q_seg, k_prefix, seg_off: int) -> int:

@@ -46,23 +46,29 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
   extern __shared__ __attribute__((aligned(8192))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const UnitChunk uc = split_unit(blockIdx.x, a.n_whole, a.n_split);
   int qt, bh;
-  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
+  decode_workgroup(uc.unit, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
   qt = a.n_tiles - 1 - qt;   // later (heavier) row tiles are scheduled first
   const int h = bh % a.n_q_heads, b = bh / a.n_q_heads, hk = h / a.group;
-  const int seg_off = a.seg_off, seg_len = a.seg_len, kv_len = seg_off + seg_len;
+  const int seg_len = a.seg_len;
   const int row0 = qt * BM, wrow0 = row0 + wave * 32 * NQ;
+  const int last_row = (row0 + BM < seg_len ? row0 + BM : seg_len) - 1;
+  // This workgroup's key tiles: all that hold keys 0 .. seg_off+last_row, or one chunk of them.  From here on keys
+  // are counted from the chunk's first key: seg_off and kv_len are relative to it.
+  int kt0, kt1;
+  chunk_range(uc, (a.seg_off + row0) / BN, (a.seg_off + last_row) / BN + 1, kt0, kt1);
+  const int seg_off = a.seg_off - BN * kt0, kv_len = seg_off + seg_len;
+  const int n_kt = kt1 - kt0;
 
   const int64_t qoff = b * a.q_sb + h * a.q_sh;
   const T *qb = reinterpret_cast<const T *>(a.q) + qoff;
   const T *dob = reinterpret_cast<const T *>(a.dout) + qoff;
   const T *ob = reinterpret_cast<const T *>(a.out) + qoff;
-  const T *kbase = reinterpret_cast<const T *>(a.k) + b * a.kv_sb + hk * a.kv_sh;
-  const T *vbase = reinterpret_cast<const T *>(a.v) + b * a.kv_sb + hk * a.kv_sh;
+  const int64_t kv_first = b * a.kv_sb + hk * a.kv_sh + (int64_t)(BN * kt0) * a.kv_ss;
+  const T *kbase = reinterpret_cast<const T *>(a.k) + kv_first;
+  const T *vbase = reinterpret_cast<const T *>(a.v) + kv_first;
   const int64_t lse_off = ((int64_t)b * a.n_q_heads + h) * seg_len;
-
-  const int last_row = (row0 + BM < seg_len ? row0 + BM : seg_len) - 1;
-  const int n_kt = (seg_off + last_row) / BN + 1;
   const lds_addr lds0 = to_lds_addr(smem);
   AsyncTilePairU<T, BN, D, 4> ld;
   ld.init(wave, lane, a.kv_ss);
@@ -86,7 +92,7 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
     }
     nd[nq] = -sum_xor32(part);
     nl[nq] = -a.lse[lse_off + rc] / a.scale;
-    if (r < seg_len && g == 0) {   // row statistics for the dK/dV kernel
+    if (r < seg_len && g == 0 && uc.chunk == 0) {   // row statistics for the dK/dV kernel
       a.delta[lse_off + r] = nl[nq];
       a.delta[a.ws_plane + lse_off + r] = nd[nq];
     }
@@ -169,6 +175,23 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
     __syncthreads();
   }
 
+  if (uc.slot >= 0) {   // a chunk: its unscaled share of the unit's dQ rows goes to the workspace
+    float *pd = a.part + (int64_t)uc.slot * (BM * D);
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+      const int rl = wave * 32 * NQ + 32 * nq + ln;   // row within the unit
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          const int d0 = 32 * db + 8 * vq + 4 * g;
+          if (d0 < D)
+            store4<float>(pd + rl * D + d0, dq[nq][db][4 * vq], dq[nq][db][4 * vq + 1], dq[nq][db][4 * vq + 2],
+                          dq[nq][db][4 * vq + 3]);
+        }
+    }
+    return;
+  }
   T *dqb = reinterpret_cast<T *>(a.dq) + qoff;
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
@@ -185,6 +208,26 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
                       dq[nq][db][4 * vq + 2] * a.scale, dq[nq][db][4 * vq + 3] * a.scale);
         }
     }
+  }
+}
+
+// Sums the chunks of the units that seg_attn_bwd_dq_kernel split along the keys: dq = scale * sum_c part_c.
+// One workgroup per split unit; a thread handles 4 consecutive head_dim elements of a row.
+template <typename T, int D, int BM>
+__global__ void __launch_bounds__(256) seg_attn_bwd_dq_merge_kernel(const AttnArgs a) {
+  int qt, bh;
+  decode_workgroup(a.n_whole + (int)blockIdx.x, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
+  qt = a.n_tiles - 1 - qt;
+  const int h = bh % a.n_q_heads, b = bh / a.n_q_heads;
+  const int row0 = qt * BM, S = a.n_split;
+  const float *pd = a.part + (int64_t)blockIdx.x * S * (BM * D);
+  T *dqb = reinterpret_cast<T *>(a.dq) + b * a.q_sb + h * a.q_sh;
+  for (int idx = threadIdx.x; idx < BM * (D / 4); idx += 256) {
+    const int rl = idx / (D / 4), c4 = idx % (D / 4), r = row0 + rl;
+    if (r >= a.seg_len) continue;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < S; ++c) acc += *reinterpret_cast<const f32x4 *>(pd + c * (BM * D) + rl * D + 4 * c4);
+    store4<T>(dqb + (int64_t)r * a.q_ss + 4 * c4, acc[0] * a.scale, acc[1] * a.scale, acc[2] * a.scale, acc[3] * a.scale);
   }
 }
 

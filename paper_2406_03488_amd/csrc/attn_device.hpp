@@ -472,6 +472,26 @@ S1F_DEV void decode_workgroup(int id, int n_tiles, int n_bh, int tile_major, int
   }
 }
 
+// Key-split.  The workgroups of a launch are handed to the chip's workgroup slots in id order; when the last
+// round of units fills only part of the slots, the launch ends with most of the chip idle for the length of one
+// unit (a row tile against its whole prefix).  The host may therefore cut each of the LAST units of a launch into
+// n_split chunks along the keys, which then run side by side; every chunk leaves a partial result in a workspace and a
+// small second kernel merges them.  The keys that every row of the unit sees in full (`full`, counted in pieces of the
+// kernel's step) are dealt out evenly; the last chunk also takes the pieces on the diagonal.
+// In: workgroup id.  Out: unit id, the chunk's piece range [begin, end) and its index in the workspace (-1: whole).
+struct UnitChunk {
+  int unit, chunk, n_chunks, slot;
+};
+S1F_DEV UnitChunk split_unit(int id, int n_whole, int n_split) {
+  if (id < n_whole) return UnitChunk{id, 0, 1, -1};
+  const int j = id - n_whole;
+  return UnitChunk{n_whole + j / n_split, j % n_split, n_split, j};
+}
+S1F_DEV void chunk_range(const UnitChunk &u, int full, int total, int &begin, int &end) {
+  begin = u.chunk * full / u.n_chunks;
+  end = u.chunk + 1 < u.n_chunks ? (u.chunk + 1) * full / u.n_chunks : total;
+}
+
 // Arguments common to the three kernels (all strides in elements of the tensor they index).
 struct AttnArgs {
   const void *q, *k, *v, *out, *dout;   // out: written by fwd, read by bwd
@@ -488,6 +508,12 @@ struct AttnArgs {
   int32_t n_tiles, n_bh;                 // launch shape: tiles per (batch, head) and number of (batch, head) pairs
   int32_t tile_major;                    // order of the workgroups within an XCD (see decode_workgroup)
   float scale;                           // 1/sqrt(head_dim)
+  // Key-split of the last units of a launch (forward and dQ kernels; see split_unit): workgroup ids below n_whole
+  // are whole units; the ids from there on come in runs of n_split chunks of one unit each.
+  int32_t n_whole, n_split;
+  float *part;                           // partial results of the chunks: [chunk id - n_whole][rows per unit][head_dim]
+  float *part_ml;                        // forward only: running maximum (log2 units) and row sum, [..][rows per unit][2]
+  int64_t part_cap;                      // host side only: most bytes of partial results a launch may plan for
 };
 
 }  // namespace s1f

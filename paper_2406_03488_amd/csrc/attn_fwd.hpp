@@ -196,20 +196,26 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   extern __shared__ __attribute__((aligned(8192))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const UnitChunk uc = split_unit(blockIdx.x, a.n_whole, a.n_split);
   int qt, bh;
-  decode_workgroup(blockIdx.x, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
+  decode_workgroup(uc.unit, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
   qt = a.n_tiles - 1 - qt;   // later (heavier) row tiles are scheduled first
   const int h = bh % a.n_q_heads, b = bh / a.n_q_heads, hk = h / a.group;
-  const int seg_off = a.seg_off, seg_len = a.seg_len, kv_len = seg_off + seg_len;
+  const int seg_len = a.seg_len;
   const int row0 = qt * BM, wrow0 = row0 + wave * 32 * NQ;
+  const int last_row = (row0 + BM < seg_len ? row0 + BM : seg_len) - 1;
+  // This workgroup's 32-key blocks: all that hold keys 0 .. seg_off+last_row, or one chunk of them.  From here on
+  // keys are counted from the chunk's first key: seg_off and kv_len are relative to it.
+  int blk0, blk1;
+  chunk_range(uc, (a.seg_off + row0) / 32, (a.seg_off + last_row) / 32 + 1, blk0, blk1);
+  const int seg_off = a.seg_off - 32 * blk0, kv_len = seg_off + seg_len;
+  const int n_blk = blk1 - blk0;
+  const int n_kt = (n_blk + KB - 1) / KB;
 
   const T *qb = reinterpret_cast<const T *>(a.q) + b * a.q_sb + h * a.q_sh;
-  const T *kbase = reinterpret_cast<const T *>(a.k) + b * a.kv_sb + hk * a.kv_sh;
-  const T *vbase = reinterpret_cast<const T *>(a.v) + b * a.kv_sb + hk * a.kv_sh;
-
-  const int last_row = (row0 + BM < seg_len ? row0 + BM : seg_len) - 1;
-  const int n_blk = (seg_off + last_row) / 32 + 1;           // 32-key blocks holding keys 0 .. seg_off+last_row
-  const int n_kt = (n_blk + KB - 1) / KB;
+  const int64_t kv_first = b * a.kv_sb + hk * a.kv_sh + (int64_t)(32 * blk0) * a.kv_ss;
+  const T *kbase = reinterpret_cast<const T *>(a.k) + kv_first;
+  const T *vbase = reinterpret_cast<const T *>(a.v) + kv_first;
 
   const lds_addr lds0 = to_lds_addr(smem);
   // The wave's share of a tile's copy is issued in KB parts, one per 32-key step, so that the waves of the
@@ -342,6 +348,29 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
     fwd_step<RD, T, false>(s, sn, o, m, l, mx, qf, rd, vblock, vblock, c, false, 0);
   }
 
+  if (uc.slot >= 0) {   // a chunk: unnormalised output rows, running maximum and row sum go to the workspace
+    float *po = a.part + (int64_t)uc.slot * (BM * D);
+    float *pml = a.part_ml + (int64_t)uc.slot * (BM * 2);
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+      const float lt = sum_xor32(l[nq]);
+      const int rl = wave * 32 * NQ + 32 * nq + ln;   // row within the unit
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          const int d0 = 32 * db + 8 * vq + 4 * g;
+          if (d0 < D)
+            store4<float>(po + rl * D + d0, o[nq][db][4 * vq], o[nq][db][4 * vq + 1], o[nq][db][4 * vq + 2],
+                          o[nq][db][4 * vq + 3]);
+        }
+      if (g == 0) {
+        pml[2 * rl] = m[nq];
+        pml[2 * rl + 1] = lt;
+      }
+    }
+    return;
+  }
   T *ob = reinterpret_cast<T *>(a.out_w) + b * a.q_sb + h * a.q_sh;
   float *lse = a.lse + ((int64_t)b * a.n_q_heads + h) * seg_len;
 #pragma unroll
@@ -362,6 +391,39 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
         }
       if (g == 0) lse[r] = (m[nq] + __builtin_amdgcn_logf(lt)) * kLn2;
     }
+  }
+}
+
+// Merges the chunks of the units that seg_attn_fwd_kernel split along the keys: with m_c, l_c, o_c the running
+// maximum (log2 units), row sum and unnormalised output row of chunk c,
+//   m = max_c m_c,  l = sum_c l_c 2^(m_c - m),  out = sum_c o_c 2^(m_c - m) / l,  lse = (m + log2 l) ln 2.
+// One workgroup per split unit; a thread handles 4 consecutive head_dim elements of a row.
+template <typename T, int D, int BM>
+__global__ void __launch_bounds__(256) seg_attn_fwd_merge_kernel(const AttnArgs a) {
+  int qt, bh;
+  decode_workgroup(a.n_whole + (int)blockIdx.x, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
+  qt = a.n_tiles - 1 - qt;
+  const int h = bh % a.n_q_heads, b = bh / a.n_q_heads;
+  const int row0 = qt * BM, S = a.n_split;
+  const float *po = a.part + (int64_t)blockIdx.x * S * (BM * D);
+  const float *pml = a.part_ml + (int64_t)blockIdx.x * S * (BM * 2);
+  T *ob = reinterpret_cast<T *>(a.out_w) + b * a.q_sb + h * a.q_sh;
+  float *lse = a.lse + ((int64_t)b * a.n_q_heads + h) * a.seg_len;
+  for (int idx = threadIdx.x; idx < BM * (D / 4); idx += 256) {
+    const int rl = idx / (D / 4), c4 = idx % (D / 4), r = row0 + rl;
+    if (r >= a.seg_len) continue;
+    float m = -INFINITY;
+    for (int c = 0; c < S; ++c) m = fmaxf(m, pml[c * (BM * 2) + 2 * rl]);
+    float l = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < S; ++c) {
+      const float w = exp2_fast(pml[c * (BM * 2) + 2 * rl] - m);
+      l += w * pml[c * (BM * 2) + 2 * rl + 1];
+      acc += w * *reinterpret_cast<const f32x4 *>(po + c * (BM * D) + rl * D + 4 * c4);
+    }
+    const float inv = 1.f / l;
+    store4<T>(ob + (int64_t)r * a.q_ss + 4 * c4, acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+    if (c4 == 0) lse[r] = (m + __builtin_amdgcn_logf(l)) * kLn2;
   }
 }
 

@@ -87,38 +87,173 @@ int row_tile_order(const s1f_desc *d, const AttnArgs &a) {
   return 2 * (int64_t)a.seg_off < (int64_t)a.seg_len || d->n_q_heads > d->n_kv_heads;
 }
 
-// One-dimensional grid of n_tiles * n_bh workgroups; the kernels decode (tile, batch*head) themselves.
+// Key-split of the last units of a launch (see split_unit in attn_device.hpp).  A launch of `units` equal-sized
+// units runs in rounds of `slots` (the workgroups the chip holds at once); its last round holds only r = units mod
+// slots of them and still lasts as long as a full one.  Cutting each of those r units into n chunks turns that round
+// into ceil(r n / slots) rounds of 1/n the length; n (at most kMaxSplit, chunks at least kMinChunkKeys keys long,
+// partial results within `cap` bytes) is chosen to minimise that, with a small charge per chunk for the merge.
+// Deterministic in (shape, device, cap): the workspace-size queries and the launches derive the same plan.
+constexpr int kMaxSplit = 8;
+constexpr int64_t kMinChunkKeys = 256;
+constexpr int64_t kMaxPartBytes = int64_t(128) << 20;      // partial results of one launch with a caller's workspace
+constexpr int64_t kStaticPartBytes = int64_t(32) << 20;    // ... with the library's built-in scratch
+struct SplitPlan {
+  int64_t n_whole = 0;        // leading workgroup ids that are whole units
+  int64_t n_split_units = 0;  // units cut into chunks
+  int n_split = 1;            // chunks per split unit
+  int64_t grid() const { return n_whole + n_split_units * n_split; }
+};
+
+SplitPlan plan_split(int64_t units, int slots, int64_t seg_off, int64_t part_bytes_per_chunk, int64_t cap) {
+  SplitPlan p;
+  p.n_whole = units;
+  if (slots <= 0 || units <= 0) return p;
+  const int64_t r = units % slots;
+  if (r == 0) return p;
+  int best = 1;
+  double best_t = 1.0;   // length of the last round in units of a whole unit's time
+  for (int n = 2; n <= kMaxSplit; ++n) {
+    if (n > seg_off / kMinChunkKeys || r * n * part_bytes_per_chunk > cap) break;
+    const double t = (double)((r * n + slots - 1) / slots) / n + 0.01 * n;
+    if (t < best_t - 1e-9) { best = n; best_t = t; }
+  }
+  if (best_t > 0.9) return p;   // not worth a second kernel
+  p.n_whole = units - r;
+  p.n_split_units = r;
+  p.n_split = best;
+  return p;
+}
+
+// Workgroups of `kernel` that the current device holds at once (0 if that cannot be found out, e.g. without a
+// device: launches are then never split).  Looked up once per kernel instantiation and device.
+template <typename K> int resident_workgroups(K kernel, int threads, int lds_bytes) {
+  static std::atomic<int> cached[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return 0;
+  }
+  int n = cached[dev].load(std::memory_order_acquire);
+  if (n > 0) return n;
+  int per_cu = 0, cus = 0;
+  if (prepare(kernel, lds_bytes) != S1F_OK ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), threads,
+                                                   (size_t)lds_bytes) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return 0;
+  }
+  n = per_cu * cus;
+  if (n > 0) cached[dev].store(n, std::memory_order_release);
+  return n;
+}
+
+// One-dimensional grid; the kernels decode (unit -> tile, batch*head; chunk) themselves.
 // `tile_major`: order of the workgroups within an XCD; chosen per kernel from the shape of the segment.
 // With `enqueue` false only the one-time preparation runs, so that a caller of several kernels can finish
 // everything that may fail before the first of them is enqueued.  The status reflects this launch only (the
 // return code of the launch call, not the runtime's sticky last error).
 template <typename K>
 int launch(K kernel, int64_t n_tiles, int64_t n_bh, int tile_major, int threads, int lds_bytes, AttnArgs a, hipStream_t st,
-           bool enqueue) {
+           bool enqueue, const SplitPlan *plan = nullptr) {
   if (n_tiles * n_bh > 0x7fffffff) return S1F_EUNSUPPORTED;
   const int rc = prepare(kernel, lds_bytes);
   if (rc != S1F_OK || !enqueue) return rc;
   a.n_tiles = (int32_t)n_tiles;
   a.n_bh = (int32_t)n_bh;
   a.tile_major = tile_major;
+  a.n_whole = (int32_t)(plan ? plan->n_whole : n_tiles * n_bh);
+  a.n_split = plan ? plan->n_split : 1;
+  const int64_t grid = plan ? plan->grid() : n_tiles * n_bh;
   void *params[] = {&a};
-  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)(n_tiles * n_bh)),
-                                       dim3(threads), params, (size_t)lds_bytes, st);
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)grid), dim3(threads), params,
+                                       (size_t)lds_bytes, st);
   return e == hipSuccess ? S1F_OK : S1F_EDEVICE;
 }
 
-template <typename T, int D> int fwd_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
-  typedef Shape<T> S;
-  typedef FwdCfg<T, D, S::FNQ, S::FKB, S::FNW> Cfg;
-  return launch(seg_attn_fwd_kernel<T, D, S::FNQ, S::FKB, S::FNW, S::FOCC>, (a.seg_len + Cfg::BM - 1) / Cfg::BM,
-                (int64_t)d->n_q_heads * d->batch, row_tile_order(d, a), Cfg::THREADS, Cfg::LDS_BYTES, a, st, enqueue);
+// The merge kernel behind a split launch: one workgroup per split unit.
+template <typename K> int launch_merge(K kernel, AttnArgs a, const SplitPlan &plan, hipStream_t st) {
+  void *params[] = {&a};
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)plan.n_split_units),
+                                       dim3(256), params, 0, st);
+  return e == hipSuccess ? S1F_OK : S1F_EDEVICE;
 }
 
-template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ---- forward ----
+template <typename T, int D> struct FwdLaunch {
+  typedef Shape<T> S;
+  typedef FwdCfg<T, D, S::FNQ, S::FKB, S::FNW> Cfg;
+  static constexpr int64_t kPartBytes = (int64_t)Cfg::BM * D * 4, kMlBytes = (int64_t)Cfg::BM * 2 * 4;
+  static auto kernel() { return seg_attn_fwd_kernel<T, D, S::FNQ, S::FKB, S::FNW, S::FOCC>; }
+  static int64_t tiles(int64_t seg_len) { return (seg_len + Cfg::BM - 1) / Cfg::BM; }
+  // `split`: the caller brought a workspace (only the bf16 kernels split; fp32 is the reference-precision mode)
+  static SplitPlan plan(const s1f_desc *d, int64_t seg_off, int64_t seg_len, bool split) {
+    const int64_t units = tiles(seg_len) * d->n_q_heads * d->batch;
+    if (!split || sizeof(T) != 2) return plan_split(units, 0, 0, 0, 0);
+    return plan_split(units, resident_workgroups(kernel(), Cfg::THREADS, Cfg::LDS_BYTES), seg_off, kPartBytes + kMlBytes,
+                      kMaxPartBytes);
+  }
+  static size_t workspace_bytes(const SplitPlan &p) {
+    const int64_t chunks = p.n_split_units * p.n_split;
+    return chunks == 0 ? 0 : align256((size_t)(chunks * kPartBytes)) + (size_t)(chunks * kMlBytes);
+  }
+};
+
+template <typename T, int D>
+int fwd_impl(const s1f_desc *d, AttnArgs a, hipStream_t st, void *workspace, size_t workspace_bytes, bool split) {
+  typedef FwdLaunch<T, D> L;
+  const SplitPlan p = L::plan(d, a.seg_off, a.seg_len, split);
+  if (L::workspace_bytes(p) > workspace_bytes) return S1F_EINVAL;
+  const int64_t chunks = p.n_split_units * p.n_split;
+  a.part = reinterpret_cast<float *>(workspace);
+  a.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + align256((size_t)(chunks * L::kPartBytes)));
+  const int64_t n_bh = (int64_t)d->n_q_heads * d->batch;
+  const int order = row_tile_order(d, a);
+  int rc = launch(L::kernel(), L::tiles(a.seg_len), n_bh, order, L::Cfg::THREADS, L::Cfg::LDS_BYTES, a, st, true, &p);
+  if (rc != S1F_OK || chunks == 0) return rc;
+  a.n_tiles = (int32_t)L::tiles(a.seg_len); a.n_bh = (int32_t)n_bh; a.tile_major = order;
+  a.n_whole = (int32_t)p.n_whole; a.n_split = p.n_split;
+  return launch_merge(seg_attn_fwd_merge_kernel<T, D, L::Cfg::BM>, a, p, st);
+}
+template <typename T, int D> size_t fwd_ws_impl(const s1f_desc *d, int64_t seg_off, int64_t seg_len) {
+  return FwdLaunch<T, D>::workspace_bytes(FwdLaunch<T, D>::plan(d, seg_off, seg_len, true));
+}
+
+// ---- backward ----
+// Workspace: the two planes of row statistics, then (256-byte aligned) the partial dQ rows of a split dQ launch.
+template <typename T, int D> struct DqLaunch {
   typedef Shape<T> S;
   typedef BwdDqCfg<T, D, S::QNQ, S::QBN> QC;
-  return launch(seg_attn_bwd_dq_kernel<T, D, S::QNQ, S::QBN, S::QOCC>, (a.seg_len + QC::BM - 1) / QC::BM,
-                (int64_t)d->n_q_heads * d->batch, row_tile_order(d, a), 256, QC::LDS_BYTES, a, st, enqueue);
+  static constexpr int64_t kPartBytes = (int64_t)QC::BM * D * 4;
+  static auto kernel() { return seg_attn_bwd_dq_kernel<T, D, S::QNQ, S::QBN, S::QOCC>; }
+  static int64_t tiles(int64_t seg_len) { return (seg_len + QC::BM - 1) / QC::BM; }
+  static SplitPlan plan(const s1f_desc *d, int64_t seg_off, int64_t seg_len, int64_t cap) {
+    const int64_t units = tiles(seg_len) * d->n_q_heads * d->batch;
+    if (sizeof(T) != 2) return plan_split(units, 0, 0, 0, 0);
+    return plan_split(units, resident_workgroups(kernel(), 256, QC::LDS_BYTES), seg_off, kPartBytes, cap);
+  }
+};
+inline size_t stat_bytes(const s1f_desc *d, int64_t seg_len) {
+  return align256(2 * (size_t)d->batch * (size_t)d->n_q_heads * (size_t)seg_len * sizeof(float));
+}
+template <typename T, int D> size_t bwd_ws_impl(const s1f_desc *d, int64_t seg_off, int64_t seg_len, int64_t cap) {
+  const SplitPlan p = DqLaunch<T, D>::plan(d, seg_off, seg_len, cap);
+  return stat_bytes(d, seg_len) + (size_t)(p.n_split_units * p.n_split * DqLaunch<T, D>::kPartBytes);
+}
+
+template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, AttnArgs a, hipStream_t st, bool enqueue) {
+  typedef DqLaunch<T, D> L;
+  const SplitPlan p = L::plan(d, a.seg_off, a.seg_len, a.part_cap);
+  a.part = reinterpret_cast<float *>(reinterpret_cast<char *>(a.delta) + stat_bytes(d, a.seg_len));
+  const int64_t n_bh = (int64_t)d->n_q_heads * d->batch;
+  const int order = row_tile_order(d, a);
+  int rc = launch(L::kernel(), L::tiles(a.seg_len), n_bh, order, 256, L::QC::LDS_BYTES, a, st, enqueue, &p);
+  if (rc != S1F_OK || !enqueue || p.n_split_units == 0) return rc;
+  a.n_tiles = (int32_t)L::tiles(a.seg_len); a.n_bh = (int32_t)n_bh; a.tile_major = order;
+  a.n_whole = (int32_t)p.n_whole; a.n_split = p.n_split;
+  return launch_merge(seg_attn_bwd_dq_merge_kernel<T, D, L::QC::BM>, a, p, st);
 }
 
 template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
@@ -151,23 +286,47 @@ template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs
 
 }  // namespace
 
-extern "C" int s1f_seg_attn_fwd(const s1f_desc *desc, const void *q_seg, const void *k_prefix, const void *v_prefix,
-                                int64_t seg_off, int64_t seg_len, void *out, float *lse, void *hip_stream) {
+namespace {
+int fwd_entry(const s1f_desc *desc, const void *q_seg, const void *k_prefix, const void *v_prefix, int64_t seg_off,
+              int64_t seg_len, void *out, float *lse, void *workspace, size_t workspace_bytes, bool split,
+              void *hip_stream) {
   int rc = check_desc(desc);
   if (rc != S1F_OK) return rc;
   if (!q_seg || !k_prefix || !v_prefix || !out || !lse) return S1F_EINVAL;
   if (!aligned16(q_seg) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(out)) return S1F_EINVAL;
+  if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return S1F_EINVAL;
   rc = check_seg(desc, seg_off, seg_len);
   if (rc != S1F_OK) return rc;
   AttnArgs a = make_args(desc, seg_off, seg_len);
   a.q = q_seg; a.k = k_prefix; a.v = v_prefix; a.out_w = out; a.lse = lse;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  S1F_DISPATCH(fwd_impl, desc, desc, a, st, true);
+  S1F_DISPATCH(fwd_impl, desc, desc, a, st, workspace, workspace_bytes, split);
+}
+size_t fwd_ws_dispatch(const s1f_desc *d, int64_t seg_off, int64_t seg_len) { S1F_DISPATCH(fwd_ws_impl, d, d, seg_off, seg_len); }
+size_t bwd_ws_dispatch(const s1f_desc *d, int64_t seg_off, int64_t seg_len, int64_t cap) {
+  S1F_DISPATCH(bwd_ws_impl, d, d, seg_off, seg_len, cap);
+}
+}  // namespace
+
+extern "C" int s1f_seg_attn_fwd(const s1f_desc *desc, const void *q_seg, const void *k_prefix, const void *v_prefix,
+                                int64_t seg_off, int64_t seg_len, void *out, float *lse, void *hip_stream) {
+  return fwd_entry(desc, q_seg, k_prefix, v_prefix, seg_off, seg_len, out, lse, nullptr, 0, false, hip_stream);
+}
+
+extern "C" size_t s1f_fwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len) {
+  if (check_desc(desc) != S1F_OK || check_seg(desc, seg_off, seg_len) != S1F_OK) return 0;
+  return fwd_ws_dispatch(desc, seg_off, seg_len);
+}
+
+extern "C" int s1f_seg_attn_fwd_ws(const s1f_desc *desc, const void *q_seg, const void *k_prefix, const void *v_prefix,
+                                   int64_t seg_off, int64_t seg_len, void *out, float *lse, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream) {
+  return fwd_entry(desc, q_seg, k_prefix, v_prefix, seg_off, seg_len, out, lse, workspace, workspace_bytes, true, hip_stream);
 }
 
 extern "C" size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len) {
   if (check_desc(desc) != S1F_OK || check_seg(desc, seg_off, seg_len) != S1F_OK) return 0;
-  return 2 * (size_t)desc->batch * (size_t)desc->n_q_heads * (size_t)seg_len * sizeof(float);
+  return bwd_ws_dispatch(desc, seg_off, seg_len, kMaxPartBytes);
 }
 
 namespace {
@@ -181,7 +340,7 @@ int bwd_dkdv_dispatch(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool
 // Validation shared by the backward entry points; fills `a` on success.
 int bwd_prepare(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix, const void *v_prefix,
                 const float *lse, int64_t seg_off, int64_t seg_len, const void *workspace, size_t workspace_bytes,
-                AttnArgs *a) {
+                AttnArgs *a, int64_t part_cap = kMaxPartBytes) {
   int rc = check_desc(desc);
   if (rc != S1F_OK) return rc;
   if (!dout || !q_seg || !k_prefix || !v_prefix || !lse || !workspace) return S1F_EINVAL;
@@ -189,7 +348,7 @@ int bwd_prepare(const s1f_desc *desc, const void *dout, const void *q_seg, const
     return S1F_EINVAL;
   rc = check_seg(desc, seg_off, seg_len);
   if (rc != S1F_OK) return rc;
-  if (workspace_bytes < s1f_bwd_workspace_bytes(desc, seg_off, seg_len)) return S1F_EINVAL;
+  if (workspace_bytes < bwd_ws_dispatch(desc, seg_off, seg_len, part_cap)) return S1F_EINVAL;
   // the asynchronous copies address the workspace with 32-bit byte offsets
   const int64_t stat_rows = (int64_t)desc->batch * desc->n_q_heads * seg_len;
   if (stat_rows > (int64_t(1) << 28)) return S1F_EUNSUPPORTED;
@@ -198,7 +357,29 @@ int bwd_prepare(const s1f_desc *desc, const void *dout, const void *q_seg, const
   a->lse = const_cast<float *>(lse);
   a->delta = reinterpret_cast<float *>(const_cast<void *>(workspace));
   a->ws_plane = stat_rows;
+  a->part_cap = part_cap;
   return S1F_OK;
+}
+
+// s1f_seg_attn_bwd; `part_cap` bounds the partial dQ rows a split dQ launch may leave behind the statistics.
+int bwd_entry(const s1f_desc *desc, const void *dout, const void *q_seg, const void *k_prefix, const void *v_prefix,
+              const void *out, const float *lse, int64_t seg_off, int64_t seg_len, void *dq, float *dk_prefix_acc,
+              float *dv_prefix_acc, void *workspace, size_t workspace_bytes, int64_t part_cap, void *hip_stream) {
+  AttnArgs a;
+  const int rc = bwd_prepare(desc, dout, q_seg, k_prefix, v_prefix, lse, seg_off, seg_len, workspace, workspace_bytes, &a,
+                             part_cap);
+  if (rc != S1F_OK) return rc;
+  if (!out || !dq || !dk_prefix_acc || !dv_prefix_acc) return S1F_EINVAL;
+  if (!aligned16(out) || !aligned16(dq) || !aligned16(dk_prefix_acc) || !aligned16(dv_prefix_acc)) return S1F_EINVAL;
+  a.out = out; a.dq = dq; a.dk_acc = dk_prefix_acc; a.dv_acc = dv_prefix_acc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  // everything that can fail short of the launches themselves happens before the first kernel is enqueued
+  int rc2 = bwd_dq_dispatch(desc, a, st, false);
+  if (rc2 == S1F_OK) rc2 = bwd_dkdv_dispatch(desc, a, st, false);
+  if (rc2 != S1F_OK) return rc2;
+  rc2 = bwd_dq_dispatch(desc, a, st, true);
+  if (rc2 != S1F_OK) return rc2;
+  return bwd_dkdv_dispatch(desc, a, st, true);
 }
 }  // namespace
 
@@ -230,20 +411,8 @@ extern "C" int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const vo
                                 const void *v_prefix, const void *out, const float *lse, int64_t seg_off,
                                 int64_t seg_len, void *dq, float *dk_prefix_acc, float *dv_prefix_acc,
                                 void *workspace, size_t workspace_bytes, void *hip_stream) {
-  AttnArgs a;
-  const int rc = bwd_prepare(desc, dout, q_seg, k_prefix, v_prefix, lse, seg_off, seg_len, workspace, workspace_bytes, &a);
-  if (rc != S1F_OK) return rc;
-  if (!out || !dq || !dk_prefix_acc || !dv_prefix_acc) return S1F_EINVAL;
-  if (!aligned16(out) || !aligned16(dq) || !aligned16(dk_prefix_acc) || !aligned16(dv_prefix_acc)) return S1F_EINVAL;
-  a.out = out; a.dq = dq; a.dk_acc = dk_prefix_acc; a.dv_acc = dv_prefix_acc;
-  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  // everything that can fail short of the launches themselves happens before the first kernel is enqueued
-  int rc2 = bwd_dq_dispatch(desc, a, st, false);
-  if (rc2 == S1F_OK) rc2 = bwd_dkdv_dispatch(desc, a, st, false);
-  if (rc2 != S1F_OK) return rc2;
-  rc2 = bwd_dq_dispatch(desc, a, st, true);
-  if (rc2 != S1F_OK) return rc2;
-  return bwd_dkdv_dispatch(desc, a, st, true);
+  return bwd_entry(desc, dout, q_seg, k_prefix, v_prefix, out, lse, seg_off, seg_len, dq, dk_prefix_acc, dv_prefix_acc,
+                   workspace, workspace_bytes, kMaxPartBytes, hip_stream);
 }
 
 // ---- the backward for callers that cannot allocate --------------------------------------------------------------
@@ -252,7 +421,9 @@ extern "C" int s1f_seg_attn_bwd(const s1f_desc *desc, const void *dout, const vo
 // (each device holds its own copy) and that address is what the kernels receive.
 namespace {
 constexpr int64_t kStaticStatRows = int64_t(1) << 21;            // batch * n_q_heads * seg_len the array holds
-static __device__ __align__(256) float scratch[2 * kStaticStatRows];   // two planes, 16 MiB per device
+// two planes of row statistics (16 MiB), then the partial dQ rows of a split dQ launch (at most kStaticPartBytes)
+constexpr size_t kStaticScratchBytes = 2 * (size_t)kStaticStatRows * sizeof(float) + (size_t)kStaticPartBytes;
+static __device__ __align__(256) float scratch[kStaticScratchBytes / sizeof(float)];
 
 std::mutex scratch_mutex;
 float *scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, null until looked up
@@ -286,8 +457,8 @@ extern "C" int s1f_seg_attn_bwd_noalloc(const s1f_desc *desc, const void *dout, 
   rc = static_scratch(&ws);
   if (rc != S1F_OK) return rc;
   // every plane entry the dK/dV kernel reads is written by the dQ kernel of the same call: nothing to clear
-  return s1f_seg_attn_bwd(desc, dout, q_seg, k_prefix, v_prefix, out, lse, seg_off, seg_len, dq, dk_prefix_acc,
-                          dv_prefix_acc, ws, 2 * (size_t)kStaticStatRows * sizeof(float), hip_stream);
+  return bwd_entry(desc, dout, q_seg, k_prefix, v_prefix, out, lse, seg_off, seg_len, dq, dk_prefix_acc, dv_prefix_acc, ws,
+                   kStaticScratchBytes, kStaticPartBytes, hip_stream);
 }
 
 extern "C" const char *s1f_strerror(int status) {

@@ -24,8 +24,19 @@ def _alloc(layout, batch, h, s, d, dt, fill=None):
     return t
 
 
+def forward(qs, kc, vc, seg_off, out, lse, with_workspace=True):
+    """s1f_seg_attn_fwd_ws with a workspace of the size the library asks for (the path the benchmark times), or the
+    plain s1f_seg_attn_fwd."""
+    if not with_workspace:
+        s1f.seg_attn_fwd(qs, kc, vc, seg_off, out, lse)
+        return
+    nbytes = s1f.fwd_workspace_bytes(qs, kc, seg_off)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
+    s1f.seg_attn_fwd_ws(qs, kc, vc, seg_off, out, lse, ws)
+
+
 def run_schedule_batched(q, k, v, dout, boundaries, dtype, capacity=None, layout="bhsd", finality=None,
-                         cache_kernels=False):
+                         cache_kernels=False, fwd_workspace=True):
     """q, dout [B, Hq, n, D]; k, v [B, Hkv, n, D] numpy fp32: B independent sequences in one set of calls.
     Returns dict of numpy fp64 results with the same leading batch dimension.
 
@@ -66,7 +77,7 @@ def run_schedule_batched(q, k, v, dout, boundaries, dtype, capacity=None, layout
         qs = alloc(hq, b - a, tdt); qs.copy_(qd[:, :, a:b])
         out = alloc(hq, b - a, tdt, float("nan"))
         lse = torch.full((nb, hq, b - a), float("nan"), dtype=torch.float32, device="cuda")
-        s1f.seg_attn_fwd(qs, kc, vc, a, out, lse)
+        forward(qs, kc, vc, a, out, lse, fwd_workspace)
         saved.append((qs, out, lse))
     outs = np.empty((nb, hq, n, d)); lses = np.empty((nb, hq, n)); dqs = np.empty((nb, hq, n, d))
     for i in reversed(range(nseg)):
@@ -92,17 +103,18 @@ def run_schedule_batched(q, k, v, dout, boundaries, dtype, capacity=None, layout
     return res
 
 
-def run_schedule(q, k, v, dout, boundaries, dtype, capacity=None, layout="bhsd", finality=None):
+def run_schedule(q, k, v, dout, boundaries, dtype, capacity=None, layout="bhsd", finality=None, fwd_workspace=True):
     """One sequence: q, dout [Hq, n, D]; k, v [Hkv, n, D] numpy fp32.  Results without a batch dimension;
     `finality` entries are (segment index, dk [Hkv, cap, D], dv)."""
     fin = [] if finality is not None else None
-    res = run_schedule_batched(q[None], k[None], v[None], dout[None], boundaries, dtype, capacity, layout, fin)
+    res = run_schedule_batched(q[None], k[None], v[None], dout[None], boundaries, dtype, capacity, layout, fin,
+                               fwd_workspace=fwd_workspace)
     if finality is not None:
         finality.extend((i, dk[0], dv[0]) for i, dk, dv in fin)
     return {name: x[0] for name, x in res.items()}
 
 
-def run_segment(q_seg, k, v, dout_seg, seg_off, dtype, layout="bhsd"):
+def run_segment(q_seg, k, v, dout_seg, seg_off, dtype, layout="bhsd", fwd_workspace=True):
     """One forward and one backward call for a single segment at offset seg_off: q_seg, dout_seg [Hq, m, D];
     k, v [Hkv, seg_off + m, D].  dk/dv are what this segment's rows alone add to zeroed accumulators."""
     hq, m, d = q_seg.shape
@@ -115,7 +127,7 @@ def run_segment(q_seg, k, v, dout_seg, seg_off, dtype, layout="bhsd"):
     out, dq = _alloc(layout, 1, hq, m, d, tdt, float("nan")), _alloc(layout, 1, hq, m, d, tdt, float("nan"))
     lse = torch.full((1, hq, m), float("nan"), dtype=torch.float32, device="cuda")
     dk_acc, dv_acc = _alloc(layout, 1, hkv, c, d, torch.float32, 0.0), _alloc(layout, 1, hkv, c, d, torch.float32, 0.0)
-    s1f.seg_attn_fwd(qs, kc, vc, seg_off, out, lse)
+    forward(qs, kc, vc, seg_off, out, lse, fwd_workspace)
     ws = torch.empty(s1f.bwd_workspace_bytes(qs, kc, seg_off), dtype=torch.uint8, device="cuda")
     s1f.seg_attn_bwd(dos, qs, kc, vc, out, lse, seg_off, dq, dk_acc, dv_acc, ws)
     torch.cuda.synchronize()

@@ -151,3 +151,27 @@ def test_random_sweep_single_segment_calls():
         out, lse = A.segment_forward(q[:, off:], k, v, off)
         dq, dk, dv = A.segment_backward(do[:, off:], q[:, off:], k, v, off)
         _check(res, {"out": out, "lse": lse, "dq": dq, "dk": dk, "dv": dv}, dtype, where=case)
+
+
+@pytest.mark.parametrize("d", [64, 80, 128])
+@pytest.mark.parametrize("hq,hkv,off,m", [(2, 1, 2100, 333), (4, 4, 700, 140), (3, 1, 4500, 129), (8, 2, 1290, 256)])
+def test_key_split_row_tiles_match_oracle(d, hq, hkv, off, m):
+    """Few row tiles behind a long prefix: the library cuts every one of them into chunks along the keys (forward
+    through its workspace entry point, dQ through the backward's workspace) and merges the partial results; the
+    result must still equal the oracle, and the forward must agree with the entry point that never splits."""
+    import torch
+    import paper_2406_03488_amd as s1f
+    from gpu_harness import errors, run_segment, to_device
+    n = off + m
+    q, k, v, do = _sequence(7000 + d + off, hq, hkv, n, d, "bf16")
+    kd = to_device(k, "bf16")[None]
+    qd = to_device(q[:, off:], "bf16")[None].contiguous()
+    assert s1f.fwd_workspace_bytes(qd, kd, off) > 0, "this shape is meant to be split"
+    assert s1f.bwd_workspace_bytes(qd, kd, off) > 2 * 4 * hq * m + 256, "this shape is meant to be split"
+    res = run_segment(q[:, off:], k, v, do[:, off:], off, "bf16")
+    out, lse = A.segment_forward(q[:, off:], k, v, off)
+    dq, dk, dv = A.segment_backward(do[:, off:], q[:, off:], k, v, off)
+    _check(res, {"out": out, "lse": lse, "dq": dq, "dk": dk, "dv": dv}, "bf16")
+    plain = run_segment(q[:, off:], k, v, do[:, off:], off, "bf16", fwd_workspace=False)
+    assert errors(res["out"], plain["out"])[0] <= 2.0 ** -7 * np.abs(plain["out"]).max()   # one bf16 rounding apart
+    assert errors(res["lse"], plain["lse"])[0] <= 1e-5
