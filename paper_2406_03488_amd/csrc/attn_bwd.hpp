@@ -42,6 +42,7 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
   constexpr int DB = KT::DPAD / 32, NSLAB = 16 / EPL, KB = BN / 32;
   constexpr int BM = 128 * NQ;
   constexpr int BLOCK_BYTES = 32 * KT::RS * 16;
+  constexpr int PF = NKS >= 3 ? 3 : 2;   // operand fragments in flight ahead of their use
 
   extern __shared__ __attribute__((aligned(8192))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
@@ -128,14 +129,21 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
         for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
           for (int v = 0; v < 16; ++v) { s[nq][v] = nl[nq]; dp[nq][v] = nd[nq]; }
+        // K and V fragments are read from LDS PF steps ahead of the matrix instructions that use them
+        {
+          Frag kf[PF], vf[PF];
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-          Frag kf, vf;
-          rd.nat2(kblock, KT::BYTES, ks, kf, vf);
+          for (int i = 0; i < PF; ++i) rd.nat2(kblock, KT::BYTES, i, kf[i], vf[i]);
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int nq = 0; nq < NQ; ++nq) {
-            s[nq] = mma(kf, qf[nq][ks], s[nq]);
-            dp[nq] = mma(vf, dof[nq][ks], dp[nq]);
+          for (int ks = 0; ks < NKS; ++ks) {
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq) {
+              s[nq] = mma(kf[ks % PF], qf[nq][ks], s[nq]);
+              dp[nq] = mma(vf[ks % PF], dof[nq][ks], dp[nq]);
+            }
+            if (ks + PF < NKS) rd.nat2(kblock, KT::BYTES, ks + PF, kf[ks % PF], vf[ks % PF]);
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
         // register v holds key kb0 + 8*(v/4) + 4*g + v%4, visible to row r iff key <= seg_off + r; only
