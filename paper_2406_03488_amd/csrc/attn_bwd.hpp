@@ -220,23 +220,28 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
 }
 
 // Sums the chunks of the units that seg_attn_bwd_dq_kernel split along the keys: dq = scale * sum_c part_c.
-// One workgroup per split unit; a thread handles 4 consecutive head_dim elements of a row.
+// Thread and grid layout as in seg_attn_fwd_merge_kernel.
 template <typename T, int D, int BM>
 __global__ void __launch_bounds__(256) seg_attn_bwd_dq_merge_kernel(const AttnArgs a) {
+  constexpr int C4 = D / 4, RG = 256 / C4, GROUPS = (BM + RG - 1) / RG;
+  const int unit = (int)blockIdx.x / GROUPS, rg = (int)blockIdx.x % GROUPS;
+  const int rl = rg * RG + (int)threadIdx.x / C4, c4 = (int)threadIdx.x % C4;
   int qt, bh;
-  decode_workgroup(a.n_whole + (int)blockIdx.x, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
+  decode_workgroup(a.n_whole + unit, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
   qt = a.n_tiles - 1 - qt;
   const int h = bh % a.n_q_heads, b = bh / a.n_q_heads;
-  const int row0 = qt * BM, S = a.n_split;
-  const float *pd = a.part + (int64_t)blockIdx.x * S * (BM * D);
+  const int r = qt * BM + rl, S = a.n_split;
+  if ((int)threadIdx.x >= RG * C4 || rl >= BM || r >= a.seg_len) return;
+  const float *pd = a.part + (int64_t)unit * S * (BM * D) + rl * D + 4 * c4;
+  f32x4 pc[kMaxChunks];
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c)
+    pc[c] = c < S ? *reinterpret_cast<const f32x4 *>(pd + c * (BM * D)) : f32x4{0.f, 0.f, 0.f, 0.f};
+  f32x4 acc = pc[0];
+#pragma unroll
+  for (int c = 1; c < kMaxChunks; ++c) acc += pc[c];
   T *dqb = reinterpret_cast<T *>(a.dq) + b * a.q_sb + h * a.q_sh;
-  for (int idx = threadIdx.x; idx < BM * (D / 4); idx += 256) {
-    const int rl = idx / (D / 4), c4 = idx % (D / 4), r = row0 + rl;
-    if (r >= a.seg_len) continue;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < S; ++c) acc += *reinterpret_cast<const f32x4 *>(pd + c * (BM * D) + rl * D + 4 * c4);
-    store4<T>(dqb + (int64_t)r * a.q_ss + 4 * c4, acc[0] * a.scale, acc[1] * a.scale, acc[2] * a.scale, acc[3] * a.scale);
-  }
+  store4<T>(dqb + (int64_t)r * a.q_ss + 4 * c4, acc[0] * a.scale, acc[1] * a.scale, acc[2] * a.scale, acc[3] * a.scale);
 }
 
 // dK/dV kernel.  NW waves of 32 keys each; Q/dO tiles of 32 rows travel through a ring of NST LDS stages.

@@ -479,6 +479,7 @@ S1F_DEV void decode_workgroup(int id, int n_tiles, int n_bh, int tile_major, int
 // small second kernel merges them.  The keys that every row of the unit sees in full (`full`, counted in pieces of the
 // kernel's step) are dealt out evenly; the last chunk also takes the pieces on the diagonal.
 // In: workgroup id.  Out: unit id, the chunk's piece range [begin, end) and its index in the workspace (-1: whole).
+constexpr int kMaxChunks = 8;   // most chunks a unit is ever cut into
 struct UnitChunk {
   int unit, chunk, n_chunks, slot;
 };

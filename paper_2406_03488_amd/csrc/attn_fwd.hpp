@@ -397,34 +397,50 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
 // Merges the chunks of the units that seg_attn_fwd_kernel split along the keys: with m_c, l_c, o_c the running
 // maximum (log2 units), row sum and unnormalised output row of chunk c,
 //   m = max_c m_c,  l = sum_c l_c 2^(m_c - m),  out = sum_c o_c 2^(m_c - m) / l,  lse = (m + log2 l) ln 2.
-// One workgroup per split unit; a thread handles 4 consecutive head_dim elements of a row.
+// A thread handles 4 consecutive head_dim elements of one row; a workgroup MergeRows<D>::RG rows of one split unit
+// (grid: split units x groups of RG rows).  All chunk loads of a thread are independent of each other.
+template <int D> struct MergeRows {
+  static constexpr int C4 = D / 4;          // threads per row
+  static constexpr int RG = 256 / C4;       // rows per workgroup
+  static constexpr int groups(int bm) { return (bm + RG - 1) / RG; }
+};
 template <typename T, int D, int BM>
 __global__ void __launch_bounds__(256) seg_attn_fwd_merge_kernel(const AttnArgs a) {
+  typedef MergeRows<D> MR;
+  const int unit = (int)blockIdx.x / MR::groups(BM), rg = (int)blockIdx.x % MR::groups(BM);
+  const int rl = rg * MR::RG + (int)threadIdx.x / MR::C4, c4 = (int)threadIdx.x % MR::C4;
   int qt, bh;
-  decode_workgroup(a.n_whole + (int)blockIdx.x, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
+  decode_workgroup(a.n_whole + unit, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
   qt = a.n_tiles - 1 - qt;
   const int h = bh % a.n_q_heads, b = bh / a.n_q_heads;
-  const int row0 = qt * BM, S = a.n_split;
-  const float *po = a.part + (int64_t)blockIdx.x * S * (BM * D);
-  const float *pml = a.part_ml + (int64_t)blockIdx.x * S * (BM * 2);
-  T *ob = reinterpret_cast<T *>(a.out_w) + b * a.q_sb + h * a.q_sh;
-  float *lse = a.lse + ((int64_t)b * a.n_q_heads + h) * a.seg_len;
-  for (int idx = threadIdx.x; idx < BM * (D / 4); idx += 256) {
-    const int rl = idx / (D / 4), c4 = idx % (D / 4), r = row0 + rl;
-    if (r >= a.seg_len) continue;
-    float m = -INFINITY;
-    for (int c = 0; c < S; ++c) m = fmaxf(m, pml[c * (BM * 2) + 2 * rl]);
-    float l = 0.f;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < S; ++c) {
-      const float w = exp2_fast(pml[c * (BM * 2) + 2 * rl] - m);
-      l += w * pml[c * (BM * 2) + 2 * rl + 1];
-      acc += w * *reinterpret_cast<const f32x4 *>(po + c * (BM * D) + rl * D + 4 * c4);
-    }
-    const float inv = 1.f / l;
-    store4<T>(ob + (int64_t)r * a.q_ss + 4 * c4, acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
-    if (c4 == 0) lse[r] = (m + __builtin_amdgcn_logf(l)) * kLn2;
+  const int r = qt * BM + rl, S = a.n_split;
+  if ((int)threadIdx.x >= MR::RG * MR::C4 || rl >= BM || r >= a.seg_len) return;
+  const float *po = a.part + (int64_t)unit * S * (BM * D) + rl * D + 4 * c4;
+  const float *pml = a.part_ml + (int64_t)unit * S * (BM * 2) + 2 * rl;
+  float mc[kMaxChunks], lc[kMaxChunks];
+  f32x4 oc[kMaxChunks];
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c) {
+    const bool on = c < S;
+    mc[c] = on ? pml[c * (BM * 2)] : -INFINITY;
+    lc[c] = on ? pml[c * (BM * 2) + 1] : 0.f;
+    oc[c] = on ? *reinterpret_cast<const f32x4 *>(po + c * (BM * D)) : f32x4{0.f, 0.f, 0.f, 0.f};
   }
+  float m = mc[0];
+#pragma unroll
+  for (int c = 1; c < kMaxChunks; ++c) m = fmaxf(m, mc[c]);
+  float l = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < kMaxChunks; ++c) {
+    const float w = exp2_fast(mc[c] - m);   // 0 for the chunks past S
+    l += w * lc[c];
+    acc += w * oc[c];
+  }
+  const float inv = 1.f / l;
+  T *ob = reinterpret_cast<T *>(a.out_w) + b * a.q_sb + h * a.q_sh;
+  store4<T>(ob + (int64_t)r * a.q_ss + 4 * c4, acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+  if (c4 == 0) a.lse[((int64_t)b * a.n_q_heads + h) * a.seg_len + r] = (m + __builtin_amdgcn_logf(l)) * kLn2;
 }
 
 }  // namespace s1f

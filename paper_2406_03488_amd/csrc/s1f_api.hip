@@ -93,7 +93,7 @@ int row_tile_order(const s1f_desc *d, const AttnArgs &a) {
 // into ceil(r n / slots) rounds of 1/n the length; n (at most kMaxSplit, chunks at least kMinChunkKeys keys long,
 // partial results within `cap` bytes) is chosen to minimise that, with a small charge per chunk for the merge.
 // Deterministic in (shape, device, cap): the workspace-size queries and the launches derive the same plan.
-constexpr int kMaxSplit = 8;
+constexpr int kMaxSplit = kMaxChunks;
 constexpr int64_t kMinChunkKeys = 256;
 constexpr int64_t kMaxPartBytes = int64_t(128) << 20;      // partial results of one launch with a caller's workspace
 constexpr int64_t kStaticPartBytes = int64_t(32) << 20;    // ... with the library's built-in scratch
@@ -171,10 +171,10 @@ int launch(K kernel, int64_t n_tiles, int64_t n_bh, int tile_major, int threads,
   return e == hipSuccess ? S1F_OK : S1F_EDEVICE;
 }
 
-// The merge kernel behind a split launch: one workgroup per split unit.
-template <typename K> int launch_merge(K kernel, AttnArgs a, const SplitPlan &plan, hipStream_t st) {
+// The merge kernel behind a split launch: `groups` workgroups (of a few rows each) per split unit.
+template <typename K> int launch_merge(K kernel, AttnArgs a, const SplitPlan &plan, int groups, hipStream_t st) {
   void *params[] = {&a};
-  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)plan.n_split_units),
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)(plan.n_split_units * groups)),
                                        dim3(256), params, 0, st);
   return e == hipSuccess ? S1F_OK : S1F_EDEVICE;
 }
@@ -215,7 +215,7 @@ int fwd_impl(const s1f_desc *d, AttnArgs a, hipStream_t st, void *workspace, siz
   if (rc != S1F_OK || chunks == 0) return rc;
   a.n_tiles = (int32_t)L::tiles(a.seg_len); a.n_bh = (int32_t)n_bh; a.tile_major = order;
   a.n_whole = (int32_t)p.n_whole; a.n_split = p.n_split;
-  return launch_merge(seg_attn_fwd_merge_kernel<T, D, L::Cfg::BM>, a, p, st);
+  return launch_merge(seg_attn_fwd_merge_kernel<T, D, L::Cfg::BM>, a, p, MergeRows<D>::groups(L::Cfg::BM), st);
 }
 template <typename T, int D> size_t fwd_ws_impl(const s1f_desc *d, int64_t seg_off, int64_t seg_len) {
   return FwdLaunch<T, D>::workspace_bytes(FwdLaunch<T, D>::plan(d, seg_off, seg_len, true));
@@ -253,7 +253,7 @@ template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, AttnArgs a, hipS
   if (rc != S1F_OK || !enqueue || p.n_split_units == 0) return rc;
   a.n_tiles = (int32_t)L::tiles(a.seg_len); a.n_bh = (int32_t)n_bh; a.tile_major = order;
   a.n_whole = (int32_t)p.n_whole; a.n_split = p.n_split;
-  return launch_merge(seg_attn_bwd_dq_merge_kernel<T, D, L::QC::BM>, a, p, st);
+  return launch_merge(seg_attn_bwd_dq_merge_kernel<T, D, L::QC::BM>, a, p, MergeRows<D>::groups(L::QC::BM), st);
 }
 
 template <typename T, int D> int bwd_dkdv_impl(const s1f_desc *d, const AttnArgs &a, hipStream_t st, bool enqueue) {
