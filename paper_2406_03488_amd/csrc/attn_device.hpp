@@ -483,10 +483,28 @@ constexpr int kMaxChunks = 8;   // most chunks a unit is ever cut into
 struct UnitChunk {
   int unit, chunk, n_chunks, slot;
 };
-S1F_DEV UnitChunk split_unit(int id, int n_whole, int n_split) {
+// The chunks keep their unit's XCD (workgroup ids go to the XCDs in turn, and decode_workgroup ties a unit to the XCD of
+// its id): with heads pinned to XCDs, chunk id j runs on XCD j mod 8 and is dealt a unit with that residue; the
+// chunks of one unit are consecutive on that XCD.  (n_whole and the number of split units are then multiples of 8.)
+S1F_DEV bool chunks_keep_xcd(int n_bh, int n_whole) { return ((n_bh | n_whole) & 7) == 0; }
+S1F_DEV UnitChunk split_unit(int id, int n_whole, int n_split, bool keep_xcd) {
   if (id < n_whole) return UnitChunk{id, 0, 1, -1};
   const int j = id - n_whole;
+  if (keep_xcd) {
+    const int q = j >> 3;
+    return UnitChunk{n_whole + ((q / n_split) << 3) + (j & 7), q % n_split, n_split, j};
+  }
   return UnitChunk{n_whole + j / n_split, j % n_split, n_split, j};
+}
+// Workspace index of chunk 0 of split unit number `unit_idx` (counted from n_whole), and the index step to its next chunk.
+S1F_DEV void chunk_slots(int unit_idx, int n_split, bool keep_xcd, int &first, int &step) {
+  if (keep_xcd) {
+    first = (((unit_idx >> 3) * n_split) << 3) + (unit_idx & 7);
+    step = 8;
+  } else {
+    first = unit_idx * n_split;
+    step = 1;
+  }
 }
 S1F_DEV void chunk_range(const UnitChunk &u, int full, int total, int &begin, int &end) {
   begin = u.chunk * full / u.n_chunks;
