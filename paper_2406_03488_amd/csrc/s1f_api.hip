@@ -302,9 +302,24 @@ int fwd_entry(const s1f_desc *desc, const void *q_seg, const void *k_prefix, con
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   S1F_DISPATCH(fwd_impl, desc, desc, a, st, workspace, workspace_bytes, split);
 }
-size_t fwd_ws_dispatch(const s1f_desc *d, int64_t seg_off, int64_t seg_len) { S1F_DISPATCH(fwd_ws_impl, d, d, seg_off, seg_len); }
+// (callers have validated the descriptor: the dispatch below always finds its kernel)
+size_t fwd_ws_dispatch(const s1f_desc *d, int64_t seg_off, int64_t seg_len) {
+  if (d->dtype != S1F_BF16) return 0;   // fp32 launches are never split
+  switch (d->head_dim) {
+    case 64: return fwd_ws_impl<bf16_t, 64>(d, seg_off, seg_len);
+    case 80: return fwd_ws_impl<bf16_t, 80>(d, seg_off, seg_len);
+    case 128: return fwd_ws_impl<bf16_t, 128>(d, seg_off, seg_len);
+  }
+  return 0;
+}
 size_t bwd_ws_dispatch(const s1f_desc *d, int64_t seg_off, int64_t seg_len, int64_t cap) {
-  S1F_DISPATCH(bwd_ws_impl, d, d, seg_off, seg_len, cap);
+  if (d->dtype != S1F_BF16) return stat_bytes(d, seg_len);
+  switch (d->head_dim) {
+    case 64: return bwd_ws_impl<bf16_t, 64>(d, seg_off, seg_len, cap);
+    case 80: return bwd_ws_impl<bf16_t, 80>(d, seg_off, seg_len, cap);
+    case 128: return bwd_ws_impl<bf16_t, 128>(d, seg_off, seg_len, cap);
+  }
+  return stat_bytes(d, seg_len);
 }
 }  // namespace
 

@@ -184,6 +184,16 @@ def test_attention_entry_points_validate_before_any_launch():
     assert fwd(_desc(), seg_off=300, seg_len=256) == 3            # past kv_capacity
     assert lib.s1f_seg_attn_fwd(None, p, p, p, 0, 1, p, p, None) == 1
 
+    def fwd_ws(desc, ws, ws_bytes):
+        return lib.s1f_seg_attn_fwd_ws(ctypes.byref(desc), p, p, p, 0, 256, p, p, ws, ws_bytes, None)
+
+    assert fwd_ws(_desc(), None, 16) == 1                          # a size without a pointer
+    assert fwd_ws(_desc(), ctypes.c_void_p(4100), 1 << 20) == 1    # misaligned workspace
+    assert fwd_ws(_desc(head_dim=96), p, 1 << 20) == 2
+    assert lib.s1f_fwd_workspace_bytes(ctypes.byref(_desc()), 0, 256) == 0       # no device here: launches are not split
+    assert lib.s1f_fwd_workspace_bytes(ctypes.byref(_desc()), 500, 256) == 0     # out of range
+    assert lib.s1f_fwd_workspace_bytes(None, 0, 256) == 0
+
     def bwd(desc, seg_off=0, seg_len=256, ws=p, ws_bytes=1 << 20):
         return lib.s1f_seg_attn_bwd(ctypes.byref(desc), p, p, p, p, p, p, seg_off, seg_len, p, p, p, ws, ws_bytes, None)
 
