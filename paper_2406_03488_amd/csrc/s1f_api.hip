@@ -24,7 +24,7 @@ template <typename T> struct Shape;
 // measured 3 % faster than one workgroup of 256 keys whose upper waves run one phase late (KNW = 8, KDIST = 2,
 // KLAG = 1, KWGS = 1), on segments of the 7b and of the gqa workload alike.
 template <> struct Shape<bf16_t> {
-  static constexpr int FNQ = 1, FKB = 1, FNW = 4, FOCC = 3, QNQ = 1, QBN = 64, QOCC = 2, KNW = 4, KDIST = 1, KLAG = 0,
+  static constexpr int FNQ = 1, FKB = 1, FNW = 4, FOCC = 3, QNQ = 1, QBN = 32, QOCC = 2, KNW = 4, KDIST = 1, KLAG = 0,
                        KWGS = 2;
 };
 template <> struct Shape<float> {
