@@ -274,10 +274,12 @@ template <typename T, int D, int NW, int DIST, int LAG> struct BwdDkdvCfg {
 // Q/dO tiles and their row statistics are copied HBM -> LDS asynchronously (no staging registers).
 //
 // A wave's work on one tile has three phases: B (S and dP on the matrix pipe), C (exp and dS on the vector
-// pipe), D (dV and dK on the matrix pipe).  The two waves that share a SIMD belong to the two halves of the
-// workgroup; with LAG = 1 the upper half runs the sequence one phase late (C and D of the previous tile,
-// then B of the current one), so that between two barriers one wave's vector phase meets the other's matrix
-// phases instead of both queueing for the same pipe.
+// pipe), D (dV and dK on the matrix pipe).  Two waves share a SIMD, and one's vector phase should meet the other's
+// matrix phases instead of both queueing for the same pipe.  Either the two belong to different workgroups (NW = 4,
+// WGS = 2: two workgroups per compute unit with barriers of their own, which also overlaps one's prologue and
+// epilogue with the other's loop; the shape the library launches for bf16), or to the two halves of one workgroup
+// (NW = 8) whose upper half, with LAG = 1, runs the sequence one phase late (C and D of the previous tile, then B of
+// the current one).
 template <typename T, int D, int NW, int DIST, int LAG, int WGS = 1>   // WGS: workgroups meant to share a compute unit
 __global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kernel(const AttnArgs a) {
   typedef Elem<T> E;
