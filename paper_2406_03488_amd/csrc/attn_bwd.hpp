@@ -389,7 +389,10 @@ __global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kerne
   // Phase B: the accumulators start from the row statistics instead of zero (register v holds row
   // r0 + 8*(v/4) + 4*g + v%4), so that s = q.k - lse/scale and dp = dO.v - delta come out of the matrix
   // pipe ready for p = exp2(c*s) and dS = p*dp.
+  // The matrix phases run at a raised wave priority, the vector phase at the default one: when the two waves of a
+  // SIMD both have instructions ready, the one feeding the matrix pipe goes first (1.3 % of the kernel, measured).
   auto phase_b = [&](State &z, const Cursor &t) {
+    __builtin_amdgcn_s_setprio(2);
     const lds_addr qblock = lds0 + t.stage * Cfg::STAGE_BYTES;   // the dO block lies QT::BYTES behind it
     const lds_addr st = stats0 + (unsigned)(t.stage * Cfg::STAT_BYTES + 16 * g);
 #pragma unroll
@@ -422,6 +425,7 @@ __global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kerne
   // Phase C.  Visible iff key <= seg_off + row and row < seg_len, row = r0 + 4g + 8*(v/4) + v%4; blocks that
   // lie wholly below the diagonal and inside the segment (nearly all of them) skip the test.
   auto phase_c = [&](State &z, const Cursor &t) {
+    __builtin_amdgcn_s_setprio(0);
     const lds_addr qblock = lds0 + t.stage * Cfg::STAGE_BYTES;
 #pragma unroll
     for (int i = PF; i < PFD; ++i) rd.tr2(qblock, QT::BYTES, i / DB, i % DB, z.tq[i], z.tdo[i]);   // rest of phase D's ring
@@ -450,6 +454,7 @@ __global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kerne
     __builtin_amdgcn_sched_barrier(0);
   };
   auto phase_d = [&](State &z, const Cursor &t) {
+    __builtin_amdgcn_s_setprio(2);
     const lds_addr qblock = lds0 + t.stage * Cfg::STAGE_BYTES;
     Frag pf, dsf;
 #pragma unroll
