@@ -47,7 +47,7 @@ __global__ void __launch_bounds__(256, OCC) seg_attn_bwd_dq_kernel(const AttnArg
   extern __shared__ __attribute__((aligned(8192))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const UnitChunk uc = split_unit(blockIdx.x, a.n_whole, a.n_split, chunks_keep_xcd(a.n_bh, a.n_whole));
+  const UnitChunk uc = split_unit(blockIdx.x, a.n_whole, a.n_split, a.n_split_units);
   int qt, bh;
   decode_workgroup(uc.unit, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
   qt = a.n_tiles - 1 - qt;   // later (heavier) row tiles are scheduled first
@@ -233,7 +233,7 @@ __global__ void __launch_bounds__(256) seg_attn_bwd_dq_merge_kernel(const AttnAr
   const int r = qt * BM + rl, S = a.n_split;
   if ((int)threadIdx.x >= RG * C4 || rl >= BM || r >= a.seg_len) return;
   int slot0, slot_step;
-  chunk_slots(unit, S, chunks_keep_xcd(a.n_bh, a.n_whole), slot0, slot_step);
+  chunk_slots(unit, a.n_split_units, slot0, slot_step);
   const float *pd = a.part + (int64_t)slot0 * (BM * D) + rl * D + 4 * c4;
   f32x4 pc[kMaxChunks];
 #pragma unroll

@@ -483,28 +483,23 @@ constexpr int kMaxChunks = 8;   // most chunks a unit is ever cut into
 struct UnitChunk {
   int unit, chunk, n_chunks, slot;
 };
-// The chunks keep their unit's XCD (workgroup ids go to the XCDs in turn, and decode_workgroup ties a unit to the XCD of
-// its id): with heads pinned to XCDs, chunk id j runs on XCD j mod 8 and is dealt a unit with that residue; the
-// chunks of one unit are consecutive on that XCD.  (n_whole and the number of split units are then multiples of 8.)
-S1F_DEV bool chunks_keep_xcd(int n_bh, int n_whole) { return ((n_bh | n_whole) & 7) == 0; }
-S1F_DEV UnitChunk split_unit(int id, int n_whole, int n_split, bool keep_xcd) {
+// Chunk-major order: the ids past n_whole first run through one chunk of every split unit, then through the next
+// chunk, so that the workgroups that start one after the other walk the SAME keys of neighbouring row tiles and
+// share them in the L2 (in unit-major order, a unit's chunks side by side, the workgroups of one key range start
+// too far apart for that: 1.5 to 1.7 times the reads from memory over a 32K-token step).  The chunk that holds the diagonal goes first: it is
+// the longest.  A chunk keeps its unit's XCD (workgroup ids go to the XCDs in turn, and decode_workgroup ties a unit
+// to the XCD of its id) whenever n_whole and the number of split units are multiples of 8, which they are when the
+// heads are pinned to XCDs.
+S1F_DEV UnitChunk split_unit(int id, int n_whole, int n_split, int n_split_units) {
   if (id < n_whole) return UnitChunk{id, 0, 1, -1};
-  const int j = id - n_whole;
-  if (keep_xcd) {
-    const int q = j >> 3;
-    return UnitChunk{n_whole + ((q / n_split) << 3) + (j & 7), q % n_split, n_split, j};
-  }
-  return UnitChunk{n_whole + j / n_split, j % n_split, n_split, j};
+  const int j = id - n_whole, pass = j / n_split_units, idx = j - pass * n_split_units;
+  const int chunk = n_split - 1 - pass;
+  return UnitChunk{n_whole + idx, chunk, n_split, chunk * n_split_units + idx};
 }
 // Workspace index of chunk 0 of split unit number `unit_idx` (counted from n_whole), and the index step to its next chunk.
-S1F_DEV void chunk_slots(int unit_idx, int n_split, bool keep_xcd, int &first, int &step) {
-  if (keep_xcd) {
-    first = (((unit_idx >> 3) * n_split) << 3) + (unit_idx & 7);
-    step = 8;
-  } else {
-    first = unit_idx * n_split;
-    step = 1;
-  }
+S1F_DEV void chunk_slots(int unit_idx, int n_split_units, int &first, int &step) {
+  first = unit_idx;
+  step = n_split_units;
 }
 S1F_DEV void chunk_range(const UnitChunk &u, int full, int total, int &begin, int &end) {
   begin = u.chunk * full / u.n_chunks;
@@ -528,9 +523,9 @@ struct AttnArgs {
   int32_t tile_major;                    // order of the workgroups within an XCD (see decode_workgroup)
   float scale;                           // 1/sqrt(head_dim)
   // Key-split of the last units of a launch (forward and dQ kernels; see split_unit): workgroup ids below n_whole
-  // are whole units; the ids from there on come in runs of n_split chunks of one unit each.
-  int32_t n_whole, n_split;
-  float *part;                           // partial results of the chunks: [chunk id - n_whole][rows per unit][head_dim]
+  // are whole units; the n_split_units units after them are cut into n_split chunks each.
+  int32_t n_whole, n_split, n_split_units;
+  float *part;                           // partial results of the chunks: [chunk][split unit][rows per unit][head_dim]
   float *part_ml;                        // forward only: running maximum (log2 units) and row sum, [..][rows per unit][2]
   int64_t part_cap;                      // host side only: most bytes of partial results a launch may plan for
 };

@@ -196,7 +196,7 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   extern __shared__ __attribute__((aligned(8192))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, ln = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const UnitChunk uc = split_unit(blockIdx.x, a.n_whole, a.n_split, chunks_keep_xcd(a.n_bh, a.n_whole));
+  const UnitChunk uc = split_unit(blockIdx.x, a.n_whole, a.n_split, a.n_split_units);
   int qt, bh;
   decode_workgroup(uc.unit, a.n_tiles, a.n_bh, a.tile_major, qt, bh);
   qt = a.n_tiles - 1 - qt;   // later (heavier) row tiles are scheduled first
@@ -416,7 +416,7 @@ __global__ void __launch_bounds__(256) seg_attn_fwd_merge_kernel(const AttnArgs 
   const int r = qt * BM + rl, S = a.n_split;
   if ((int)threadIdx.x >= MR::RG * MR::C4 || rl >= BM || r >= a.seg_len) return;
   int slot0, slot_step;
-  chunk_slots(unit, S, chunks_keep_xcd(a.n_bh, a.n_whole), slot0, slot_step);
+  chunk_slots(unit, a.n_split_units, slot0, slot_step);
   const float *po = a.part + (int64_t)slot0 * (BM * D) + rl * D + 4 * c4;
   const float *pml = a.part_ml + (int64_t)slot0 * (BM * 2) + 2 * rl;
   float mc[kMaxChunks], lc[kMaxChunks];

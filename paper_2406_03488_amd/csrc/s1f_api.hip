@@ -172,6 +172,7 @@ int launch(K kernel, int64_t n_tiles, int64_t n_bh, int tile_major, int threads,
   a.tile_major = tile_major;
   a.n_whole = (int32_t)(plan ? plan->n_whole : n_tiles * n_bh);
   a.n_split = plan ? plan->n_split : 1;
+  a.n_split_units = (int32_t)(plan ? plan->n_split_units : 0);
   const int64_t grid = plan ? plan->grid() : n_tiles * n_bh;
   void *params[] = {&a};
   const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)grid), dim3(threads), params,
@@ -222,7 +223,7 @@ int fwd_impl(const s1f_desc *d, AttnArgs a, hipStream_t st, void *workspace, siz
   int rc = launch(L::kernel(), L::tiles(a.seg_len), n_bh, order, L::Cfg::THREADS, L::Cfg::LDS_BYTES, a, st, true, &p);
   if (rc != S1F_OK || chunks == 0) return rc;
   a.n_tiles = (int32_t)L::tiles(a.seg_len); a.n_bh = (int32_t)n_bh; a.tile_major = order;
-  a.n_whole = (int32_t)p.n_whole; a.n_split = p.n_split;
+  a.n_whole = (int32_t)p.n_whole; a.n_split = p.n_split; a.n_split_units = (int32_t)p.n_split_units;
   return launch_merge(seg_attn_fwd_merge_kernel<T, D, L::Cfg::BM>, a, p, MergeRows<D>::groups(L::Cfg::BM), st);
 }
 template <typename T, int D> size_t fwd_ws_impl(const s1f_desc *d, int64_t seg_off, int64_t seg_len) {
@@ -260,7 +261,7 @@ template <typename T, int D> int bwd_dq_impl(const s1f_desc *d, AttnArgs a, hipS
   int rc = launch(L::kernel(), L::tiles(a.seg_len), n_bh, order, 256, L::QC::LDS_BYTES, a, st, enqueue, &p);
   if (rc != S1F_OK || !enqueue || p.n_split_units == 0) return rc;
   a.n_tiles = (int32_t)L::tiles(a.seg_len); a.n_bh = (int32_t)n_bh; a.tile_major = order;
-  a.n_whole = (int32_t)p.n_whole; a.n_split = p.n_split;
+  a.n_whole = (int32_t)p.n_whole; a.n_split = p.n_split; a.n_split_units = (int32_t)p.n_split_units;
   return launch_merge(seg_attn_bwd_dq_merge_kernel<T, D, L::QC::BM>, a, p, MergeRows<D>::groups(L::QC::BM), st);
 }
 
