@@ -181,6 +181,48 @@ def test_key_split_row_tiles_match_oracle(d, hq, hkv, off, m):
     assert errors(res["lse"], plain["lse"])[0] <= 1e-5
 
 
+def _rising(seed, hq, hkv, n, d, dtype, levels=4):
+    """Inputs whose scores climb along the sequence: key j carries a_j * u (a_j rising from 0 to 2 in `levels` steps,
+    u a fixed vector of +-1) and query r carries c_r * u with c_r in [-2, 2], both on top of 0.6 * N(0, 1)
+    noise.  Row r's scaled scores step up by 2 c_r * sqrt(d) / (levels - 1) from level to level (tens of nats for the
+    rows with large c_r, far beyond what N(0, 1) operands ever produce), and fall as steeply for the rows with c_r < 0."""
+    q, k, v, do = _sequence(seed, hq, hkv, n, d, dtype)
+    u = np.where(S.head_tensor(seed + 1, "q", 0, 1, d, "f32")[0] >= 0, 1.0, -1.0).astype(np.float32)
+    a = 2.0 * (np.arange(n) * levels // n).astype(np.float32) / (levels - 1)
+    c = np.clip(S.tensor(seed + 2, "q", hq, n, 1, "f32")[..., 0] * 1.5, -2.0, 2.0)
+    k = 0.6 * k + a[None, :, None] * u
+    q = 0.6 * q + c[:, :, None] * u
+    if dtype == "bf16":
+        q, k = S.round_to_bf16(q), S.round_to_bf16(k)
+    return q.astype(np.float32), k.astype(np.float32), v, do
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("bf16", 80), ("f32", 128)])
+def test_rising_scores_raise_the_running_maximum(dtype, d):
+    """The forward keeps a running row maximum and rescales its accumulators when a later block of keys exceeds it
+    by a wide margin; N(0, 1) operands never make it do so.  Here the scores of many rows climb by tens of nats along
+    the keys (and fall as far for others, whose late probabilities underflow to zero), through several segments and
+    through a launch whose row tiles are cut along the keys, where the chunks of one row differ as much in their
+    maxima."""
+    from gpu_harness import run_schedule, run_segment
+    hq, hkv, n = 4, 2, BOUNDS[-1]
+    q, k, v, do = _rising(910 + d, hq, hkv, n, d, dtype)
+    scores = np.einsum("hrd,hjd->hrj", q.astype(np.float64), np.repeat(k, hq // hkv, axis=0)) / np.sqrt(d)
+    rows = range(n // 2, n)
+    climb = np.array([[scores[h, r, 32:r + 1].max() - scores[h, r, :32].max() for r in rows] for h in range(hq)])
+    fall = np.array([[scores[h, r, r - 31:r + 1].max() - scores[h, r, :32].max() for r in rows] for h in range(hq)])
+    assert (climb > 10.0).mean() > 0.15 and (fall < -10.0).mean() > 0.15   # the data does what the test is about
+    res = run_schedule(q, k, v, do, BOUNDS, dtype)
+    _check(res, _oracle(q, k, v, do), dtype, where="schedule: ")
+    if dtype == "bf16":   # few row tiles behind a long prefix: forward and dQ launches are split along the keys
+        off, m = 2100, 333
+        q, k, v, do = _rising(920 + d, 2, 1, off + m, d, dtype)
+        res = run_segment(q[:, off:], k, v, do[:, off:], off, dtype)
+        out, lse = A.segment_forward(q[:, off:], k, v, off)
+        dq, dk, dv = A.segment_backward(do[:, off:], q[:, off:], k, v, off)
+        _check(res, {"out": out, "lse": lse, "dq": dq, "dk": dk, "dv": dv}, dtype, where="key-split: ")
+
+
 def test_results_do_not_depend_on_the_run():
     """No kernel uses atomics and every accumulator element has one owner, so the same call on the same data must give
     the same bits every time, key-split launches included (their merge adds the chunks in a fixed order)."""
