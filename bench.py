@@ -117,8 +117,10 @@ class Stage:
         self.dk = torch.empty((1, w.n_kv_heads, n, d), device="cuda", dtype=torch.float32)
         self.dv = torch.empty_like(self.dk)
         self.lse_flat = torch.empty(w.n_q_heads * n, device="cuda", dtype=torch.float32)
-        self.ws = torch.empty(2 * w.n_q_heads * (n + 64) + (129 << 18), device="cuda", dtype=torch.float32)   # statistics + 129 MiB of partial rows
-        self.fwd_ws = torch.empty(130 << 20, device="cuda", dtype=torch.uint8)
+        # workspaces at the library's upper limits (row statistics + 512 MiB of partial rows; 513 MiB forward), so that
+        # any list of boundaries fits; every call still checks its own size
+        self.ws = torch.empty(2 * w.n_q_heads * (n + 64) + (513 << 18), device="cuda", dtype=torch.float32)
+        self.fwd_ws = torch.empty(514 << 20, device="cuda", dtype=torch.uint8)
         self.events = []     # (kind, segment, start, end) recorded inside timed steps
 
     def boundaries(self, n_seg=None, kind=None):

@@ -137,7 +137,7 @@ int s1f_seg_attn_fwd_ws(const s1f_desc *desc, const void *q_seg, const void *k_p
                         int64_t seg_off, int64_t seg_len, void *out, float *lse, void *workspace,
                         size_t workspace_bytes, void *hip_stream);
 /* Bytes s1f_seg_attn_fwd_ws needs for this call shape on the current device (0: none, or invalid arguments).  At most
- * 129 MiB.  The answer depends on the device's compute-unit count, so ask on the device that will run the call. */
+ * 513 MiB.  The answer depends on the device's compute-unit count, so ask on the device that will run the call. */
 size_t s1f_fwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t seg_len);
 
 /* Backward of one segment (derivative of Eq. 3; order and accumulation per Sections 3.1-3.2).
@@ -152,7 +152,7 @@ size_t s1f_fwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t se
  *             [seg_off, seg_off+seg_len) hold final gradients.
  *   workspace device scratch of at least s1f_bwd_workspace_bytes(desc, seg_off, seg_len) bytes
  *             (two fp32 values per query row and head: -lse/scale and -rowsum(dout * out), the row
- *             statistics the dK/dV kernel starts its products from; behind them up to 128 MiB of partial dQ
+ *             statistics the dK/dV kernel starts its products from; behind them up to 512 MiB of partial dQ
  *             rows when the dQ kernel cuts its last row tiles into chunks along the keys, as
  *             s1f_seg_attn_fwd_ws does); contents are undefined afterwards.
  * Errors as above, plus S1F_EINVAL if workspace is NULL or workspace_bytes is too small, and
@@ -184,7 +184,7 @@ size_t s1f_bwd_workspace_bytes(const s1f_desc *desc, int64_t seg_off, int64_t se
 /* s1f_seg_attn_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
  * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments (without the
  * workspace), same kernels; dK/dV bit-identical, dQ identical up to the rounding order of the key-split (the
- * built-in scratch leaves room for 32 MiB of partial dQ rows, s1f_seg_attn_bwd's workspace for 128 MiB, so the
+ * built-in scratch leaves room for 32 MiB of partial dQ rows, s1f_seg_attn_bwd's workspace for 512 MiB, so the
  * two may cut a launch differently); the row statistics go to a device array built into the
  * library (48 MiB per GPU: 16 MiB of row statistics and 32 MiB for partial dQ rows; held until the process ends)
  * instead of a caller-owned workspace.  The call

@@ -99,12 +99,17 @@ int row_tile_order(const s1f_desc *d, const AttnArgs &a) {
 // units runs in rounds of `slots` (the workgroups the chip holds at once); its last round holds only r = units mod
 // slots of them and still lasts as long as a full one.  Cutting each of those r units into n chunks turns that round
 // into ceil(r n / slots) rounds of 1/n the length; n (at most kMaxSplit, chunks at least kMinChunkKeys keys long,
-// partial results within `cap` bytes) is chosen to minimise that, with a small charge per chunk for the merge.
-// Deterministic in (shape, device, cap): the workspace-size queries and the launches derive the same plan.
+// partial results within `cap` bytes) is chosen to minimise that plus what the chunks cost: their own start-up and
+// the merge kernel, which reads every partial result once, both measured against the time a whole unit takes
+// (its keys times the kernel's time per key).  Deterministic in (shape, device, cap): the workspace-size queries
+// and the launches derive the same plan.
 constexpr int kMaxSplit = kMaxChunks;
 constexpr int64_t kMinChunkKeys = 256;
-constexpr int64_t kMaxPartBytes = int64_t(128) << 20;      // partial results of one launch with a caller's workspace
+constexpr int64_t kMaxPartBytes = int64_t(512) << 20;      // partial results of one launch with a caller's workspace
 constexpr int64_t kStaticPartBytes = int64_t(32) << 20;    // ... with the library's built-in scratch
+constexpr double kChunkStartup = 0.004;                    // a chunk's prologue and epilogue, in whole-unit times
+constexpr double kMergeSeconds = 12e-6, kMergeBytesPerSecond = 2.5e12;   // the merge kernel: fixed part, read rate
+constexpr double kFwdSecondsPerKey = 0.035e-6, kDqSecondsPerKey = 0.05e-6;   // a 128-row tile against one key
 struct SplitPlan {
   int64_t n_whole = 0;        // leading workgroup ids that are whole units
   int64_t n_split_units = 0;  // units cut into chunks
@@ -112,20 +117,22 @@ struct SplitPlan {
   int64_t grid() const { return n_whole + n_split_units * n_split; }
 };
 
-SplitPlan plan_split(int64_t units, int slots, int64_t seg_off, int64_t part_bytes_per_chunk, int64_t cap) {
+SplitPlan plan_split(int64_t units, int slots, int64_t seg_off, double unit_seconds, int64_t part_bytes_per_chunk,
+                     int64_t cap) {
   SplitPlan p;
   p.n_whole = units;
-  if (slots <= 0 || units <= 0) return p;
+  if (slots <= 0 || units <= 0 || unit_seconds <= 0) return p;
   const int64_t r = units % slots;
   if (r == 0) return p;
   int best = 1;
   double best_t = 1.0;   // length of the last round in units of a whole unit's time
   for (int n = 2; n <= kMaxSplit; ++n) {
     if (n > seg_off / kMinChunkKeys || r * n * part_bytes_per_chunk > cap) break;
-    const double t = (double)((r * n + slots - 1) / slots) / n + 0.01 * n;
+    const double merge = (kMergeSeconds + (double)(r * n * part_bytes_per_chunk) / kMergeBytesPerSecond) / unit_seconds;
+    const double t = (double)((r * n + slots - 1) / slots) / n + kChunkStartup * n + merge;
     if (t < best_t - 1e-9) { best = n; best_t = t; }
   }
-  if (best_t > 0.9) return p;   // not worth a second kernel
+  if (best_t > 0.95) return p;   // not worth a second kernel
   p.n_whole = units - r;
   p.n_split_units = r;
   p.n_split = best;
@@ -200,9 +207,9 @@ template <typename T, int D> struct FwdLaunch {
   // `split`: the caller brought a workspace (only the bf16 kernels split; fp32 is the reference-precision mode)
   static SplitPlan plan(const s1f_desc *d, int64_t seg_off, int64_t seg_len, bool split) {
     const int64_t units = tiles(seg_len) * d->n_q_heads * d->batch;
-    if (!split || sizeof(T) != 2) return plan_split(units, 0, 0, 0, 0);
-    return plan_split(units, resident_workgroups(kernel(), Cfg::THREADS, Cfg::LDS_BYTES), seg_off, kPartBytes + kMlBytes,
-                      kMaxPartBytes);
+    if (!split || sizeof(T) != 2) return plan_split(units, 0, 0, 0, 0, 0);
+    return plan_split(units, resident_workgroups(kernel(), Cfg::THREADS, Cfg::LDS_BYTES), seg_off,
+                      kFwdSecondsPerKey * (double)(seg_off + seg_len / 2), kPartBytes + kMlBytes, kMaxPartBytes);
   }
   static size_t workspace_bytes(const SplitPlan &p) {
     const int64_t chunks = p.n_split_units * p.n_split;
@@ -240,8 +247,9 @@ template <typename T, int D> struct DqLaunch {
   static int64_t tiles(int64_t seg_len) { return (seg_len + QC::BM - 1) / QC::BM; }
   static SplitPlan plan(const s1f_desc *d, int64_t seg_off, int64_t seg_len, int64_t cap) {
     const int64_t units = tiles(seg_len) * d->n_q_heads * d->batch;
-    if (sizeof(T) != 2) return plan_split(units, 0, 0, 0, 0);
-    return plan_split(units, resident_workgroups(kernel(), 256, QC::LDS_BYTES), seg_off, kPartBytes, cap);
+    if (sizeof(T) != 2) return plan_split(units, 0, 0, 0, 0, 0);
+    return plan_split(units, resident_workgroups(kernel(), 256, QC::LDS_BYTES), seg_off,
+                      kDqSecondsPerKey * (double)(seg_off + seg_len / 2), kPartBytes, cap);
   }
 };
 inline size_t stat_bytes(const s1f_desc *d, int64_t seg_len) {

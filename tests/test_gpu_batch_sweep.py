@@ -157,7 +157,7 @@ def test_random_sweep_single_segment_calls():
 
 
 @pytest.mark.parametrize("d", [64, 80, 128])
-@pytest.mark.parametrize("hq,hkv,off,m", [(2, 1, 2100, 333), (4, 4, 700, 140), (3, 1, 4500, 129), (8, 2, 1290, 256),
+@pytest.mark.parametrize("hq,hkv,off,m", [(2, 1, 2100, 333), (4, 4, 1800, 140), (3, 1, 4500, 129), (8, 2, 1290, 256),
                                           (2, 2, 3000, 1)])
 def test_key_split_row_tiles_match_oracle(d, hq, hkv, off, m):
     """Few row tiles behind a long prefix: the library cuts every one of them into chunks along the keys (forward
