@@ -11,9 +11,10 @@
 // K/V tiles of BN = 32*KB keys go from HBM straight into a 3-stage ring of swizzled LDS tiles (no register
 // staging); tile j+2 is in flight while tiles j and j+1 are consumed, with one workgroup barrier per tile.
 // The loop advances in steps of one 32-key block and is software-pipelined inside each wave: the score
-// product of block k+1 (matrix pipe) is issued together with the exponentials of block k (vector pipe),
-// then the PV product of block k follows.  Key blocks wholly above the shifted diagonal are never
-// visited; blocks wholly below it run a step without any masking code.
+// product of block k+1 (matrix pipe) is issued together with the row sums and operand packing of block k's
+// probabilities (vector pipe), then the PV product of block k together with the maximum and the exponentials
+// of block k+1 (see fwd_step).  Key blocks wholly above the shifted diagonal are never visited; blocks wholly
+// below it run a step without any masking code.
 #pragma once
 #include "attn_device.hpp"
 
@@ -76,16 +77,30 @@ template <int NQ> S1F_DEV void fwd_row_max(const f32x16 (&s)[NQ], float (&mx)[NQ
   }
 }
 
-// One pipelined step over block k, whose scores are in `s` with m already covering them:
-//   phase 1   sn = scores of block k+1 (matrix pipe)  ||  p = exp2(s*c - m), row sums (vector pipe)
-//   phase 2   O += P V of block k (matrix pipe)        ||  mask and row maximum of sn (vector pipe)
+// Probabilities of a block from its scores, against the running maximum m (log2 units): p = 2^(s*c - m).
+template <int NQ> S1F_DEV void fwd_probs(f32x16 (&p)[NQ], const f32x16 (&s)[NQ], const float (&m)[NQ], float c) {
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) p[nq][v] = exp2_fast(fmaf(s[nq][v], c, -m[nq]));
+}
+
+// One pipelined step over block k, whose probabilities (against m) are in `p`:
+//   phase 1   sn = scores of block k+1 (matrix pipe)  ||  row sums of p, p packed into operand slabs (vector pipe)
+//   phase 2   O += P V of block k (matrix pipe)        ||  maximum of sn, p = 2^(sn*c - m): block k+1's probabilities
+// The probabilities of block k+1 are computed against the CURRENT m, before anyone knows whether m has to be raised
+// for them: the caller checks mx afterwards and, in the rare case that it must raise m, rescales O and l and
+// recomputes p from sn (which this step leaves untouched).  That way the loop carries the probabilities in the
+// registers they were written to; carrying the SCORES of block k+1 over instead (exponentials at the start of the
+// next step) cost a 16-register copy per step and measured 3 % slower.
 // Operand fragments are read from LDS kPrefetch matrix instructions ahead of their use (the V fragments
 // of phase 2 start arriving during the last slots of phase 1).  No scheduling fences: the compiler keeps the
-// reads ahead by itself here, and with fences per slot the kernel measured 0.5-1 % slower.  On return mx holds the row maxima of block k+1 in log2 units.
+// reads ahead by itself here, and with fences per slot the kernel measured 0.5-1 % slower.  On return mx holds the
+// row maxima of block k+1 in log2 units.
 //   mask_next: block k+1 crosses the diagonal of the wave's rows
 //   lim0_next = (absolute row of this lane's query in query block 0) - (first key of block k+1) - 4g
 template <typename RD, typename T, bool HAS_NEXT, int NQ, int NKS, int DB>
-S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], const float (&m)[NQ], float (&l)[NQ],
+S1F_DEV void fwd_step(f32x16 (&p)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], const float (&m)[NQ], float (&l)[NQ],
                       float (&mx)[NQ], const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd,
                       lds_addr kblock_next, lds_addr vblock, float c, bool mask_next, int lim0_next
                       ) {
@@ -96,6 +111,7 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
   static_assert(NKS >= PF && NV >= PF, "prefetch ring deeper than the products");
 
   Frag vf[PF];
+  Frag pf[NQ][NSLAB];
   float rs[NQ];
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) rs[nq] = 0.f;
@@ -117,17 +133,11 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
         const int i = ks + PF - NKS;
         vf[i] = rd.tr(vblock, i / DB, i % DB);
       }
-      // this slot's share of the 16 exponentials per query block.  (The compiler moves these below the mask branch,
-      // next to their uses in phase 2, so the generated code runs the score product and then the vector phase; pinning
-      // them to their slots here was measured 3-7 % slower, with three waves per SIMD overlapping the two anyway.)
+      // this slot's share of the row sums
 #pragma unroll
       for (int v = 16 * ks / NKS; v < 16 * (ks + 1) / NKS; ++v)
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-          const float p = exp2_fast(fmaf(s[nq][v], c, -m[nq]));
-          s[nq][v] = p;
-          rs[nq] += p;
-        }
+        for (int nq = 0; nq < NQ; ++nq) rs[nq] += p[nq][v];
     }
   } else {
 #pragma unroll
@@ -135,14 +145,14 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = exp2_fast(fmaf(s[nq][v], c, -m[nq]));
-        s[nq][v] = p;
-        rs[nq] += p;
-      }
+      for (int v = 0; v < 16; ++v) rs[nq] += p[nq][v];
   }
 #pragma unroll
-  for (int nq = 0; nq < NQ; ++nq) l[nq] += rs[nq];
+  for (int nq = 0; nq < NQ; ++nq) {
+    l[nq] += rs[nq];
+#pragma unroll
+    for (int t = 0; t < NSLAB; ++t) pf[nq][t] = block_slab<T>(p[nq], t);
+  }
   // Blocks that cross the diagonal of this wave's rows get their mask here, in a branch of its own that holds
   // no matrix instruction: two instances of the whole step (with and without mask code) in one loop body make
   // the compiler keep the output accumulators in two places and copy all 64 registers on every step.
@@ -160,20 +170,20 @@ S1F_DEV void fwd_step(f32x16 (&s)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
   for (int nq = 0; nq < NQ; ++nq) mxv[nq] = -INFINITY;
 #pragma unroll
   for (int t = 0; t < NSLAB; ++t) {
-    Frag pf[NQ];
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) pf[nq] = block_slab<T>(s[nq], t);
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       const int i = t * DB + db;
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq) o[nq][db] = mma(vf[i % PF], pf[nq], o[nq][db]);
+      for (int nq = 0; nq < NQ; ++nq) o[nq][db] = mma(vf[i % PF], pf[nq][t], o[nq][db]);
       if (i + PF < NV) vf[i % PF] = rd.tr(vblock, (i + PF) / DB, (i + PF) % DB);
-      if (HAS_NEXT) {   // this slot's share of masking and maximum over the next block's 16 scores per query block
+      if (HAS_NEXT) {   // this slot's share of the next block's 16 scores per query block: maximum, probabilities
 #pragma unroll
         for (int v = 16 * i / NV; v < 16 * (i + 1) / NV; ++v)
 #pragma unroll
-          for (int nq = 0; nq < NQ; ++nq) mxv[nq] = fmaxf(mxv[nq], sn[nq][v]);
+          for (int nq = 0; nq < NQ; ++nq) {
+            mxv[nq] = fmaxf(mxv[nq], sn[nq][v]);
+            p[nq][v] = exp2_fast(fmaf(sn[nq][v], c, -m[nq]));
+          }
       }
     }
   }
@@ -282,6 +292,7 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   fwd_row_max(s, mx, c);
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) m[nq] = mx[nq];   // key 0 is visible to every row: finite
+  fwd_probs(s, s, m, c);   // from here on `s` holds the probabilities of the current block
 
   // The steady loop never touches O except through the matrix pipe.  When some row of the wave has to
   // raise its running maximum the loop is left, O and l are rescaled, and the loop is entered again.
@@ -326,10 +337,7 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
       if ((k + 1) % KB == 0) st_next = st_next == 2 ? 0 : st_next + 1;
       bool raise = false;
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq) {
-        s[nq] = sn[nq];
-        raise = raise || (mx[nq] > m[nq] + kRescaleTau);
-      }
+      for (int nq = 0; nq < NQ; ++nq) raise = raise || (mx[nq] > m[nq] + kRescaleTau);
       if (__builtin_amdgcn_ballot_w64(raise) != 0) { raise_any = true; break; }
     }
     if (!raise_any) break;
@@ -342,6 +350,7 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
 #pragma unroll
       for (int db = 0; db < DB; ++db) o[nq][db] = o[nq][db] * alpha;
     }
+    fwd_probs(s, sn, m, c);   // the current block's probabilities again, against the raised maxima
   }
   {   // last block: no next scores to compute
     const lds_addr vblock = lds0 + st_cur * Cfg::STAGE_BYTES + KT::BYTES + (k % KB) * BLOCK_BYTES;
