@@ -430,25 +430,29 @@ __global__ void __launch_bounds__(64 * NW, WGS * NW / 4) seg_attn_bwd_dkdv_kerne
 #pragma unroll
     for (int i = PF; i < PFD; ++i) rd.tr2(qblock, QT::BYTES, i / DB, i % DB, z.tq[i], z.tdo[i]);   // rest of phase D's ring
     __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float p = exp2_fast(z.s[v] * c);
+      z.s[v] = p;
+      z.dp[v] = p * z.dp[v];
+    }
+    // Tiles on the diagonal or at the end of the segment: entries above the diagonal and rows past the segment are
+    // set to zero afterwards, in a branch that holds nothing else (whatever the exponential made of them, infinity
+    // included, is overwritten).  One instance of the arithmetic above keeps p and dS in place: with a masked and an
+    // unmasked copy of it the compiler moved all 16 dS registers on every step.
     const bool edge = (wkey0 + 31 > seg_off + t.r0) || (t.r0 + 32 > seg_len);
     if (edge) {
+      asm volatile("" ::: "memory");   // keeps this a branch
       const int fl = fresh(lane), fg = fl >> 5;
       const int lo = wkey0 + (fl & 31) - seg_off - t.r0 - 4 * fg;   // need 8*(v/4)+v%4 >= lo
       const int hi = seg_len - t.r0 - 4 * fg;                       // and  8*(v/4)+v%4 <  hi
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int rr = 8 * (v >> 2) + (v & 3);
-        float p = exp2_fast(z.s[v] * c);
-        if (rr < lo || rr >= hi) p = 0.f;
-        z.s[v] = p;
-        z.dp[v] = p * z.dp[v];
-      }
-    } else {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = exp2_fast(z.s[v] * c);
-        z.s[v] = p;
-        z.dp[v] = p * z.dp[v];
+        if (rr < lo || rr >= hi) {
+          z.s[v] = 0.f;
+          z.dp[v] = 0.f;
+        }
       }
     }
     __builtin_amdgcn_sched_barrier(0);
