@@ -21,11 +21,17 @@
 
 namespace s1f {
 
-// Lazy rescaling: the running maximum m of a row is only raised when the new block's maximum exceeds it by
-// more than kRescaleTau (in log2 units).  Probabilities are then at most 2^kRescaleTau instead of 1, which
-// fp32 sums and bf16 operands hold without loss, and the accumulator rescale (a pass over every O
-// register) leaves the steady-state loop: it runs only when some row of the wave needs it.
+// Lazy rescaling: the running maximum m of a row is raised only when a new block makes its probabilities
+// 2^(s*c - m) large, and the steady loop finds that out from their SUM, which it needs anyway, instead of from their
+// maximum: a lane adds up the probabilities of its 16 keys of the block, and if that sum exceeds 2^kRescaleTau in
+// any lane of the wave (infinity included: the exponentials are taken before anyone has looked), the loop is left,
+// the block's row maxima are computed, the rows whose maximum exceeds m by more than kRescaleTau - 4 (a sum over 16
+// keys above 2^tau needs one of them above 2^(tau-4)) take it as their new m, O and l are rescaled and the block's
+// probabilities recomputed.  Otherwise every probability is at most 2^kRescaleTau, which fp32 sums and bf16
+// operands hold without loss.  The accumulator rescale (a pass over every O register) and the maximum (a chain of
+// its own through all 16 scores, plus a lane exchange) thereby leave the steady loop.
 constexpr float kRescaleTau = 8.0f;
+constexpr float kRescaleLimit = 256.0f;   // 2^kRescaleTau
 
 template <typename T, int D, int NQ, int KB, int NW> struct FwdCfg {
   static constexpr int BM = 32 * NQ * NW;
@@ -77,31 +83,37 @@ template <int NQ> S1F_DEV void fwd_row_max(const f32x16 (&s)[NQ], float (&mx)[NQ
   }
 }
 
-// Probabilities of a block from its scores, against the running maximum m (log2 units): p = 2^(s*c - m).
-template <int NQ> S1F_DEV void fwd_probs(f32x16 (&p)[NQ], const f32x16 (&s)[NQ], const float (&m)[NQ], float c) {
+// Probabilities of a block from its scores, against the running maximum m (log2 units): p = 2^(s*c - m); rs = the
+// sum over this lane's 16 keys.
+template <int NQ>
+S1F_DEV void fwd_probs(f32x16 (&p)[NQ], const f32x16 (&s)[NQ], const float (&m)[NQ], float c, float (&rs)[NQ]) {
 #pragma unroll
-  for (int nq = 0; nq < NQ; ++nq)
+  for (int nq = 0; nq < NQ; ++nq) {
+    rs[nq] = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) p[nq][v] = exp2_fast(fmaf(s[nq][v], c, -m[nq]));
+    for (int v = 0; v < 16; ++v) {
+      p[nq][v] = exp2_fast(fmaf(s[nq][v], c, -m[nq]));
+      rs[nq] += p[nq][v];
+    }
+  }
 }
 
-// One pipelined step over block k, whose probabilities (against m) are in `p`:
-//   phase 1   sn = scores of block k+1 (matrix pipe)  ||  row sums of p, p packed into operand slabs (vector pipe)
-//   phase 2   O += P V of block k (matrix pipe)        ||  maximum of sn, p = 2^(sn*c - m): block k+1's probabilities
+// One pipelined step over block k, whose probabilities (against m) are in `p` and already counted in l:
+//   phase 1   sn = scores of block k+1 (matrix pipe)  ||  p packed into operand slabs (vector pipe)
+//   phase 2   O += P V of block k (matrix pipe)        ||  p = 2^(sn*c - m): block k+1's probabilities, and their sums rs
 // The probabilities of block k+1 are computed against the CURRENT m, before anyone knows whether m has to be raised
-// for them: the caller checks mx afterwards and, in the rare case that it must raise m, rescales O and l and
-// recomputes p from sn (which this step leaves untouched).  That way the loop carries the probabilities in the
-// registers they were written to; carrying the SCORES of block k+1 over instead (exponentials at the start of the
-// next step) cost a 16-register copy per step and measured 3 % slower.
+// for them: the caller looks at rs afterwards (see kRescaleTau) and, in the rare case that it must raise m, rescales
+// O and l and recomputes p from sn (which this step leaves untouched); otherwise it adds rs to l.  That way the
+// loop carries the probabilities in the registers they were written to; carrying the SCORES of block k+1 over
+// instead (exponentials at the start of the next step) cost a 16-register copy per step and measured 3 % slower.
 // Operand fragments are read from LDS kPrefetch matrix instructions ahead of their use (the V fragments
 // of phase 2 start arriving during the last slots of phase 1).  No scheduling fences: the compiler keeps the
-// reads ahead by itself here, and with fences per slot the kernel measured 0.5-1 % slower.  On return mx holds the
-// row maxima of block k+1 in log2 units.
+// reads ahead by itself here, and with fences per slot the kernel measured 0.5-1 % slower.
 //   mask_next: block k+1 crosses the diagonal of the wave's rows
 //   lim0_next = (absolute row of this lane's query in query block 0) - (first key of block k+1) - 4g
 template <typename RD, typename T, bool HAS_NEXT, int NQ, int NKS, int DB>
-S1F_DEV void fwd_step(f32x16 (&p)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], const float (&m)[NQ], float (&l)[NQ],
-                      float (&mx)[NQ], const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd,
+S1F_DEV void fwd_step(f32x16 (&p)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], const float (&m)[NQ], float (&rs)[NQ],
+                      const typename Elem<T>::Frag (&qf)[NQ][NKS], const RD &rd,
                       lds_addr kblock_next, lds_addr vblock, float c, bool mask_next, int lim0_next
                       ) {
   typedef typename Elem<T>::Frag Frag;
@@ -112,9 +124,6 @@ S1F_DEV void fwd_step(f32x16 (&p)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
 
   Frag vf[PF];
   Frag pf[NQ][NSLAB];
-  float rs[NQ];
-#pragma unroll
-  for (int nq = 0; nq < NQ; ++nq) rs[nq] = 0.f;
   if (HAS_NEXT) {
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
@@ -133,26 +142,15 @@ S1F_DEV void fwd_step(f32x16 (&p)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
         const int i = ks + PF - NKS;
         vf[i] = rd.tr(vblock, i / DB, i % DB);
       }
-      // this slot's share of the row sums
-#pragma unroll
-      for (int v = 16 * ks / NKS; v < 16 * (ks + 1) / NKS; ++v)
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) rs[nq] += p[nq][v];
     }
   } else {
 #pragma unroll
     for (int i = 0; i < PF; ++i) vf[i] = rd.tr(vblock, i / DB, i % DB);
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) rs[nq] += p[nq][v];
   }
 #pragma unroll
-  for (int nq = 0; nq < NQ; ++nq) {
-    l[nq] += rs[nq];
+  for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
     for (int t = 0; t < NSLAB; ++t) pf[nq][t] = block_slab<T>(p[nq], t);
-  }
   // Blocks that cross the diagonal of this wave's rows get their mask here, in a branch of its own that holds
   // no matrix instruction: two instances of the whole step (with and without mask code) in one loop body make
   // the compiler keep the output accumulators in two places and copy all 64 registers on every step.
@@ -165,9 +163,8 @@ S1F_DEV void fwd_step(f32x16 (&p)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
         if (8 * (v >> 2) + (v & 3) > lim0_next + 32 * nq) sn[nq][v] = -INFINITY;
   }
 
-  float mxv[NQ];
 #pragma unroll
-  for (int nq = 0; nq < NQ; ++nq) mxv[nq] = -INFINITY;
+  for (int nq = 0; nq < NQ; ++nq) rs[nq] = 0.f;
 #pragma unroll
   for (int t = 0; t < NSLAB; ++t) {
 #pragma unroll
@@ -176,20 +173,16 @@ S1F_DEV void fwd_step(f32x16 (&p)[NQ], f32x16 (&sn)[NQ], f32x16 (&o)[NQ][DB], co
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) o[nq][db] = mma(vf[i % PF], pf[nq][t], o[nq][db]);
       if (i + PF < NV) vf[i % PF] = rd.tr(vblock, (i + PF) / DB, (i + PF) % DB);
-      if (HAS_NEXT) {   // this slot's share of the next block's 16 scores per query block: maximum, probabilities
+      if (HAS_NEXT) {   // this slot's share of the next block's 16 probabilities per query block
 #pragma unroll
         for (int v = 16 * i / NV; v < 16 * (i + 1) / NV; ++v)
 #pragma unroll
           for (int nq = 0; nq < NQ; ++nq) {
-            mxv[nq] = fmaxf(mxv[nq], sn[nq][v]);
             p[nq][v] = exp2_fast(fmaf(sn[nq][v], c, -m[nq]));
+            rs[nq] += p[nq][v];
           }
       }
     }
-  }
-  if (HAS_NEXT) {
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) mx[nq] = max_xor32(mxv[nq]) * c;
   }
 }
 
@@ -292,7 +285,10 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
   fwd_row_max(s, mx, c);
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) m[nq] = mx[nq];   // key 0 is visible to every row: finite
-  fwd_probs(s, s, m, c);   // from here on `s` holds the probabilities of the current block
+  float rs[NQ];
+  fwd_probs(s, s, m, c, rs);   // from here on `s` holds the probabilities of the current block, l their sums
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) l[nq] = rs[nq];
 
   // The steady loop never touches O except through the matrix pipe.  When some row of the wave has to
   // raise its running maximum the loop is left, O and l are rescaled, and the loop is entered again.
@@ -331,30 +327,35 @@ __global__ void __launch_bounds__(64 * NW, OCC) seg_attn_fwd_kernel(const AttnAr
       const int lim0n = seg_off + wrow0 + ln - 32 * kn - 4 * g;
       // the last block always crosses the diagonal; earlier ones do if their last key is past the wave's first row
       const bool mask_next = kn + 1 == n_blk || 32 * kn + 31 > seg_off + wrow0;
-      fwd_step<RD, T, true>(s, sn, o, m, l, mx, qf, rd, kblock_next, vblock, c, mask_next, lim0n);
+      fwd_step<RD, T, true>(s, sn, o, m, rs, qf, rd, kblock_next, vblock, c, mask_next, lim0n);
       k = kn;
       st_cur = st_next;
       if ((k + 1) % KB == 0) st_next = st_next == 2 ? 0 : st_next + 1;
       bool raise = false;
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq) raise = raise || (mx[nq] > m[nq] + kRescaleTau);
+      for (int nq = 0; nq < NQ; ++nq) raise = raise || !(rs[nq] <= kRescaleLimit);
       if (__builtin_amdgcn_ballot_w64(raise) != 0) { raise_any = true; break; }
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) l[nq] += rs[nq];
     }
     if (!raise_any) break;
+    fwd_row_max(sn, mx, c);
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
-      const float m_up = mx[nq] > m[nq] + kRescaleTau ? mx[nq] : m[nq];
+      const float m_up = mx[nq] > m[nq] + (kRescaleTau - 4.f) ? mx[nq] : m[nq];
       const float alpha = exp2_fast(m[nq] - m_up);   // exactly 1 for rows that keep their maximum
       m[nq] = m_up;
       l[nq] *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db) o[nq][db] = o[nq][db] * alpha;
     }
-    fwd_probs(s, sn, m, c);   // the current block's probabilities again, against the raised maxima
+    fwd_probs(s, sn, m, c, rs);   // the current block's probabilities again, against the raised maxima
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) l[nq] += rs[nq];
   }
   {   // last block: no next scores to compute
     const lds_addr vblock = lds0 + st_cur * Cfg::STAGE_BYTES + KT::BYTES + (k % KB) * BLOCK_BYTES;
-    fwd_step<RD, T, false>(s, sn, o, m, l, mx, qf, rd, vblock, vblock, c, false, 0);
+    fwd_step<RD, T, false>(s, sn, o, m, rs, qf, rd, vblock, vblock, c, false, 0);
   }
 
   if (uc.slot >= 0) {   // a chunk: unnormalised output rows, running maximum and row sum go to the workspace
