@@ -9,7 +9,7 @@ the timed region.  Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gqa|30b|7b|2.7b|30b-uniform|tiny]
 
 The headline workload is the largest one of the contract that fits one GPU (gqa: 131072 tokens, 32 segments, 64
-query heads on 8 K/V heads); the 7b and 30b workloads are run briefly in the same command and reported under
+query heads on 8 K/V heads); the 7b, 30b and 2.7b workloads are run briefly in the same command and reported under
 "other_workloads".
 """
 import argparse
@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="gqa")
-    ap.add_argument("--others", default="7b,30b", help="workloads reported briefly next to the headline ('' for none)")
+    ap.add_argument("--others", default="7b,30b,2.7b", help="workloads reported briefly next to the headline ('' for none)")
     ap.add_argument("--constant-data", action="store_true",
                     help="fill Q, K, V and dO with one constant instead of N(0,1): same instructions, hardly a bit "
                          "toggling (shows how much of the kernels' time is the chip's power limit)")
@@ -446,7 +446,9 @@ def main():
     # the other workloads of the target range, briefly: same step, same kernels
     others = {}
     for name in [x for x in args.others.split(",") if x and x != w.name]:
-        st2, r2, _, _ = measure_workload(S.WORKLOADS[name], torch, s1f, 3, 1, args.constant_data)
+        short = S.WORKLOADS[name].seq_len < 32768      # a step of a few milliseconds: more of them
+        st2, r2, _, _ = measure_workload(S.WORKLOADS[name], torch, s1f, 20 if short else 3, 3 if short else 1,
+                                         args.constant_data)
         if not args.no_unsegmented:
             r2.update(unsegmented_report(st2, r2["ms_per_step"], 2))
         r2["kernels"] = {k: {"alg_tflops": v["alg_tflops"], "ms_per_step": v["ms_per_step"],
