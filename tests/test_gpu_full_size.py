@@ -93,3 +93,42 @@ def test_full_size_workload_sampled_against_row_oracle(name, second_keys):
         assert mx <= BF16_MAXABS and fro <= BF16_RELFRO, ("dk", j0, mx, fro)
         mx, fro = _errors(stage.dv[0, g, j0:j1].cpu().numpy(), dv_ref)
         assert mx <= BF16_MAXABS and fro <= BF16_RELFRO, ("dv", j0, mx, fro)
+
+
+def test_one_long_launch_without_segments():
+    """A single launch over a whole sequence that is many rounds of row tiles long (128 tiles x 56 heads): the
+    forward and dQ kernels then order their workgroups head by head although the launch starts at offset 0.  Sampled
+    rows and keys against the row oracle, invariants on every head."""
+    import torch
+    import bench
+    import s1f_synth as S
+    import paper_2406_03488_amd as s1f
+    from oracle import rows
+
+    w = S.Workload("one-pass", 16384, 1, 56, 56, 128, 7168, "bf16", "uniform", 20240611)
+    stage = bench.Stage(w, torch, s1f)
+    bounds = stage.step()
+    torch.cuda.synchronize()
+    assert bounds == [0, w.seq_len]
+    n, d = w.seq_len, w.head_dim
+    for t in (stage.out, stage.dq, stage.dk, stage.dv):
+        assert torch.isfinite(t).all()
+    do_sum = stage.dout.float().sum(dim=2).double().cpu().numpy()
+    assert _errors(stage.dv.double().sum(dim=2).cpu().numpy(), do_sum)[1] <= BF16_RELFRO
+    assert stage.dk.double().sum(dim=2).abs().max().item() <= 1e-2 * stage.dk.double().abs().sum(dim=2).max().item()
+    for h in (0, 29, 55):
+        q = stage.q[0, h:h + 1].float().cpu().numpy(); do = stage.dout[0, h:h + 1].float().cpu().numpy()
+        k = stage.k[0, h:h + 1].float().cpu().numpy(); v = stage.v[0, h:h + 1].float().cpu().numpy()
+        for r0, r1 in [(0, 24), (4090, 4110), (n - 24, n)]:
+            print(f"  head {h} rows {r0}..{r1}", flush=True)
+            o_ref, lse_ref = rows.forward_rows(q, k, v, 0, r0, r1)
+            dq_ref = rows.dq_rows(q, k, v, do, 0, r0, r1)
+            for name, got, ref in (("out", stage.out, o_ref), ("dq", stage.dq, dq_ref)):
+                mx, fro = _errors(got[0, h, r0:r1].float().cpu().numpy(), ref)
+                assert mx <= BF16_MAXABS and fro <= BF16_RELFRO, (name, h, r0, mx, fro)
+            assert np.abs(stage.lse_flat.view(w.n_q_heads, n)[h, r0:r1].cpu().numpy() - lse_ref).max() <= 1e-3
+        j0, j1 = n - 40, n
+        dk_ref, dv_ref = rows.dkdv_keys(q, k, v, do, 0, j0, j1)
+        for name, got, ref in (("dk", stage.dk, dk_ref), ("dv", stage.dv, dv_ref)):
+            mx, fro = _errors(got[0, h, j0:j1].cpu().numpy(), ref)
+            assert mx <= BF16_MAXABS and fro <= BF16_RELFRO, (name, h, mx, fro)
