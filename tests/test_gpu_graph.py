@@ -1,5 +1,6 @@
 """A whole step (K/V append, forward of every segment, backward in reverse order, gradient emit) recorded once into
-a HIP graph and replayed: every replay must reproduce the eager results bit for bit (the kernels use no atomics),
+a HIP graph and replayed (launches split along the keys and their merge kernels included): every replay must
+reproduce the eager results bit for bit (the kernels use no atomics),
 with eager work and synchronisations between the replays, and on fresh inputs written into the same buffers."""
 import numpy as np
 import pytest
@@ -13,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 
 def test_step_in_a_graph_matches_eager_on_every_replay():
-    hq, hkv, n, d, dtype = 4, 2, 700, 128, "bf16"
+    hq, hkv, n, d, dtype = 4, 2, 3300, 128, "bf16"
     bounds = s1f.partition(n, 3, 64, 4)
     segs = list(zip(bounds[:-1], bounds[1:]))
 
@@ -28,11 +29,14 @@ def test_step_in_a_graph_matches_eager_on_every_replay():
     dk_out = torch.empty_like(kc); dv_out = torch.empty_like(kc)
     lses = [torch.empty((1, hq, b - a), dtype=torch.float32, device="cuda") for a, b in segs]
     wss = [torch.empty(s1f.bwd_workspace_bytes(qd[:, :, a:b], kc, a), dtype=torch.uint8, device="cuda") for a, b in segs]
+    fwd_bytes = [s1f.fwd_workspace_bytes(qd[:, :, a:b], kc, a) for a, b in segs]
+    assert max(fwd_bytes) > 0, "a launch of this step is meant to be split along the keys (merge kernels in the graph)"
+    fwss = [torch.empty(nb, dtype=torch.uint8, device="cuda") if nb else None for nb in fwd_bytes]
 
     def step():
-        for (a, b), lse in zip(segs, lses):
+        for (a, b), lse, fws in zip(segs, lses, fwss):
             s1f.kv_append(kd[:, :, a:b], vd[:, :, a:b], a, kc, vc)
-            s1f.seg_attn_fwd(qd[:, :, a:b], kc, vc, a, out[:, :, a:b], lse)
+            s1f.seg_attn_fwd_ws(qd[:, :, a:b], kc, vc, a, out[:, :, a:b], lse, fws)
         dk_acc.zero_(); dv_acc.zero_()          # a fill kernel, not a memset node
         for i in reversed(range(len(segs))):
             a, b = segs[i]
