@@ -14,8 +14,10 @@
  *
  * Conventions common to all device entry points
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library allocates nothing,
- *     keeps no pointer after return, and has no global state beyond a per-device "large LDS enabled" flag
- *     per kernel (re-entrant).
+ *     keeps no caller pointer after return, and its only global state is what it asked the runtime once per
+ *     device and kernel and remembers: that the kernel may use more than 64 KiB of LDS, how many of its
+ *     workgroups the device holds at once, and the address of the scratch array built into the library
+ *     (s1f_seg_attn_bwd_noalloc).  Calls are re-entrant.
  *   - Layout is [batch, head, sequence, head_dim] with head_dim contiguous; the other three strides
  *     are passed in ELEMENTS through s1f_desc.  q, out, dout, dq share the q_* strides; k, v share the
  *     kv_* strides; dk_prefix_acc, dv_prefix_acc share the kv_* strides too (in fp32 elements).
